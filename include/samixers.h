@@ -1,0 +1,183 @@
+/* samixers.h -- C ABI of the MI355X (gfx950) decode-step library for the four token mixers of
+ * "Super Apriel: One Checkpoint, Many Speeds": Gated DeltaNet (GDN), Kimi Delta Attention (KDA),
+ * full GQA attention (FA) and sliding-window GQA attention (SWA), plus the per-request placement
+ * dispatcher over a stack of mixer layers.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".  The caller owns every
+ *     buffer; no hot call allocates or frees device memory.
+ *   - `stream` is a hipStream_t (NULL = the null stream).  Calls only enqueue work on it and never
+ *     synchronise; buffers must stay alive until that work has run.
+ *   - bf16 tensors are passed as `const void*` (16-bit patterns, round-to-nearest-even of fp32).
+ *   - Every entry returns a status.  Host-checkable violations (null or misaligned pointers, bad
+ *     shapes, unsupported sizes) are reported BEFORE anything is enqueued and leave outputs
+ *     untouched.  Values that live in device memory (seq_lens, page tables, index lists) are not
+ *     validated.  sa_last_error() gives a message for the last failing call of the calling thread.
+ *   - Pointers must be 16-byte aligned (4-byte for int32 lists and per-head gate scalars).
+ */
+#ifndef SAMIXERS_H
+#define SAMIXERS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int sa_status;
+enum {
+  SA_OK = 0,
+  SA_EINVAL = -1,       /* null/misaligned pointer, inconsistent shape, bad placement string */
+  SA_EUNSUPPORTED = -2, /* a size outside what the kernels are built for                      */
+  SA_EHIP = -3,         /* a HIP call or launch failed                                        */
+  SA_EWORKSPACE = -4    /* workspace too small                                                */
+};
+
+/* Message of the last failure on this thread; static storage, never freed by the caller. */
+const char* sa_last_error(void);
+int sa_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Recurrent mixers (Appendix B, "Gated DeltaNet (GDN)" and "Kimi Delta Attention (KDA)").
+ *
+ * For every processed batch row b, state head h and t = 0..T-1 in order, with S the dk x dv state:
+ *     GDN:  Sbar = alpha[b,t,h] * S                 KDA:  Sbar[i,:] = alpha[b,t,h,i] * S[i,:]
+ *     u = Sbar^T k;   S = Sbar + beta[b,t,h] * k (v - u)^T;   out[b,t,h,:] = scale * S^T q
+ * which is the paper's S_t = alpha_t (I - beta_t k k^T) S_{t-1} + beta_t k v^T (GDN) and
+ * S_t = (I - beta_t k k^T) diag(alpha_t) S_{t-1} + beta_t k v^T (KDA).  The read-out uses the state
+ * after the write of step t (the paper prints no read-out; this is the reading taken).
+ *
+ *   q, k      bf16 [B,T,Hk,dk]   state head h reads q/k head h / (H/Hk); H % Hk == 0
+ *   v         bf16 [B,T,H,dv]
+ *   alpha     fp32 [B,T,H] (gdn) or [B,T,H,dk] (kda), each in (0,1]
+ *   beta      fp32 [B,T,H]
+ *   state_in  fp32 tiles, tile (slot,h) at ((slot*H)+h)*dk*dv, row-major [dk][dv]
+ *   state_out same layout; may equal state_in (in place).  It receives the state after n_commit
+ *             steps (0 <= n_commit <= T; n_commit = 0 copies the tile), so a verify pass over T
+ *             drafted tokens can keep state_in intact and commit only the accepted prefix.
+ *   out       fp32 [B,T,H,dv]
+ *   slot_idx  int32 [B] or NULL: batch row -> state slot (NULL = identity)
+ *   req_idx   int32 [n_req] or NULL: the batch rows to process (NULL = rows 0..B-1, n_req ignored);
+ *             rows not listed are not touched.  A row must not be listed twice.
+ * Supported: (dk,dv) in {(64,64),(128,128)}, 1 <= T <= 8.  B = 0 or n_req = 0 is a no-op.
+ */
+sa_status gdn_decode_step(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                          const float* state_in, float* state_out, float* out,
+                          const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                          int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream);
+sa_status kda_decode_step(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                          const float* state_in, float* state_out, float* out,
+                          const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                          int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Paged KV cache (Section 6, "Heterogeneous state": KV caches grow with the sequence for FA and are
+ * bounded at the window for SWA; the paper fixes no in-page order, the one below is this library's).
+ *
+ * Pages hold 16 tokens.  A pool is [n_pages][Hkv] blocks of 16*D bf16 (4 KiB at D = 128):
+ *   K block  [D/8][16 tokens][8 dims]              element (token j, dim d) at ((d/8)*16 + j)*8 + d%8
+ *   V block  [D/16][4 token groups][16 dims][4]    element (j, d) at (((d/16)*4 + j/4)*16 + d%16)*4 + j%4
+ * page_table int32 [B,max_pages]: logical page -> physical page; entries for pages no live token
+ * falls in may be -1 and are never read.
+ *
+ * n_pages is the pool size; a table entry outside [0,n_pages) that attn_decode does meet is clamped
+ * into the pool (the result is then meaningless, but no access leaves the pool).  Slots of a page
+ * that hold no live token may contain any bit pattern, NaN included.
+ *
+ * kv_append writes T new tokens per sequence: token i of row b goes to position positions[b] + i;
+ * a token whose position is at or beyond max_pages*16, or whose page is unmapped, is skipped.
+ *   k_new, v_new  bf16 [B,T,Hkv,D] (token-major, as a projection produces them)
+ */
+sa_status kv_append(const void* k_new, const void* v_new, void* kpool, void* vpool, int n_pages,
+                    const int32_t* page_table, int max_pages, const int32_t* positions, int B, int T, int Hkv, int D,
+                    int page_size, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * GQA decode attention (Appendix B, "Full Attention (FA)" and "Sliding Window Attention (SWA)").
+ *
+ * For every processed row b with L = seq_lens[b] (the count includes the T newest tokens, whose K/V
+ * are already in the cache), new token i in [0,T) and query head h (KV head h / (Hq/Hkv)):
+ *     hi = L - T + i + 1,  lo = window > 0 ? max(0, hi - window) : 0
+ *     out[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h,:] . K_j) V_j   over cached positions j in [lo,hi)
+ * i.e. window <= 0 is full attention, window = w attends to the w most recent positions including
+ * the token itself.  Rows with hi <= 0 give zeros.  seq_lens above max_seq_len are treated as
+ * max_seq_len (max_seq_len is the host-side bound used to plan the split over pages).
+ *
+ *   q          bf16 [B,T,Hq,D]            out  fp32 [B,T,Hq,D]
+ *   seq_lens   int32 [B]                  req_idx as for the recurrent mixers
+ *   workspace  at least attn_decode_workspace_bytes(...) bytes, 16-byte aligned; holds the per-split
+ *              partial results (running maximum, normaliser, unnormalised output) that a second
+ *              kernel merges in a fixed order, so results are run-to-run deterministic.
+ * Supported: D = 128, page_size = 16, T * (Hq/Hkv) <= 16.
+ */
+size_t attn_decode_workspace_bytes(int n_req, int T, int Hq, int Hkv, int D, int max_seq_len, int window);
+sa_status attn_decode(const void* q, const void* kpool, const void* vpool, int n_pages,
+                      const int32_t* page_table, int max_pages, const int32_t* seq_lens, const int32_t* req_idx, int n_req, float* out,
+                      int B, int T, int Hq, int Hkv, int D, int page_size, int max_seq_len, int window, float scale,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Placement decode (Section 6, "Per-request placement switching": each request names a placement,
+ * a placement names one mixer per layer, and the layer dispatches on it with no global state).
+ *
+ * A placement is a NUL-terminated string with one character per layer: F (full attention),
+ * S (sliding window), K (KDA), G (GDN).  A plan groups the B requests of a batch per (layer, mixer)
+ * and keeps the index lists in device memory; it is the only object the library allocates.
+ */
+typedef struct sa_plan sa_plan;
+
+typedef struct {
+  int H, Hk, dk, dv;             /* recurrent mixers                      */
+  int Hq, Hkv, D, page_size;     /* attention mixers                      */
+} sa_shapes;
+
+typedef struct {                 /* one per layer; every pointer is a device pointer indexed by request */
+  const void* q;                 /* recurrent: bf16 [B,T,Hk,dk]           */
+  const void* k;                 /*            bf16 [B,T,Hk,dk]           */
+  const void* v;                 /*            bf16 [B,T,H,dv]            */
+  const float* alpha_scalar;     /* GDN gate   fp32 [B,T,H]               */
+  const float* alpha_vec;        /* KDA gate   fp32 [B,T,H,dk]            */
+  const float* beta;             /*            fp32 [B,T,H]               */
+  float* state;                  /* recurrent tiles of this layer, updated in place */
+  const int32_t* slot_idx;       /* request -> state slot, or NULL        */
+  const void* q_attn;            /* attention: bf16 [B,T,Hq,D]            */
+  const void* kpool;             /* this layer's K pool (new tokens already appended) */
+  const void* vpool;
+  int n_pages;                   /* pages in each pool                    */
+  const int32_t* page_table;     /* int32 [B,max_pages]                   */
+  const int32_t* seq_lens;       /* int32 [B]                             */
+  int max_pages;
+  int max_seq_len;
+  float* out;                    /* fp32 [B,T,H,dv] == [B,T,Hq,D] (needs H*dv == Hq*D) */
+} sa_layer_io;
+
+/* placements: host array of n_placements strings, each of length L.  placement_id: host int32 [B],
+ * values in [0,n_placements).  Errors: SA_EINVAL for a wrong length, an unknown character or an id
+ * out of range. */
+sa_status placement_plan_create(const char* const* placements, int n_placements, int L,
+                                const int32_t* placement_id, int B, sa_plan** plan_out);
+void placement_plan_destroy(sa_plan* plan);
+/* Number of requests that run mixer `mixer` ('F','S','K','G') at layer `layer`; -1 on bad arguments. */
+int placement_plan_count(const sa_plan* plan, int layer, char mixer);
+size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, int T, int max_seq_len, int window);
+/* io: host array of L descriptors.  Enqueues, layer by layer, one launch per mixer present in that
+ * layer over that mixer's request list.  Recurrent layers commit all T steps in place. */
+sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,
+                           float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Measurement helpers (not part of the method).
+ */
+enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5, SA_K_COUNT = 6 };
+/* While enabled, every launch of the kernels above is bracketed by HIP events on its stream. */
+void sa_prof_enable(int on);
+/* Waits for the recorded events of `kernel`, returns their count and summed duration, and forgets them. */
+sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms);
+/* Plain streaming copy of n_bytes (multiple of 16) used to calibrate bandwidth counters. */
+sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAMIXERS_H */

@@ -1,0 +1,113 @@
+// Error reporting, launch profiling and the calibration copy kernel of libsamixers.
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+
+namespace {
+
+thread_local char g_error[512] = "";
+
+struct EventPair {
+  hipEvent_t start, stop;
+};
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<EventPair> g_prof[SA_K_COUNT];
+
+}  // namespace
+
+namespace sa {
+
+sa_status fail(sa_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+sa_status check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SA_EHIP, "%s: %s", what, hipGetErrorString(e));
+  return SA_OK;
+}
+
+ProfScope::ProfScope(int kernel_id, hipStream_t s) : kernel(kernel_id), stream(s) {
+  if (!g_prof_on) return;
+  if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) {
+    start = stop = nullptr;
+    return;
+  }
+  (void)hipEventRecord(start, stream);
+}
+
+ProfScope::~ProfScope() {
+  if (!start) return;
+  (void)hipEventRecord(stop, stream);
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  g_prof[kernel].push_back({start, stop});
+}
+
+}  // namespace sa
+
+extern "C" {
+
+const char* sa_last_error(void) { return g_error; }
+
+int sa_version(void) { return 100; }
+
+void sa_prof_enable(int on) { g_prof_on = on != 0; }
+
+sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms) {
+  SA_REQUIRE(kernel >= 0 && kernel < SA_K_COUNT, SA_EINVAL, "sa_prof_read: unknown kernel id %d", kernel);
+  SA_REQUIRE(n_launches && total_ms, SA_EINVAL, "sa_prof_read: null output pointer");
+  std::vector<EventPair> taken;
+  {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    taken.swap(g_prof[kernel]);
+  }
+  float sum = 0.f;
+  sa_status st = SA_OK;
+  for (const EventPair& p : taken) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(p.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.start, p.stop);
+    if (e != hipSuccess) st = sa::fail(SA_EHIP, "sa_prof_read: %s", hipGetErrorString(e));
+    sum += ms;
+    (void)hipEventDestroy(p.start);
+    (void)hipEventDestroy(p.stop);
+  }
+  *n_launches = static_cast<int>(taken.size());
+  *total_ms = sum;
+  return st;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Grid-stride copy, 16 bytes per lane per iteration.
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+
+extern "C" sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, void* stream) {
+  SA_REQUIRE(src && dst, SA_EINVAL, "sa_copy_bytes: null pointer");
+  SA_REQUIRE(sa::aligned(src, 16) && sa::aligned(dst, 16) && n_bytes % 16 == 0, SA_EINVAL,
+             "sa_copy_bytes: pointers and size must be multiples of 16 bytes");
+  if (n_bytes == 0) return SA_OK;
+  size_t n16 = n_bytes / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  {
+    sa::ProfScope prof(SA_K_COPY, s);
+    copy_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(static_cast<const uint4*>(src),
+                                                                          static_cast<uint4*>(dst), n16);
+  }
+  return sa::check_launch("sa_copy_bytes");
+}

@@ -1,0 +1,135 @@
+// Per-request placement dispatch over a stack of mixer layers (host logic only).
+//
+// Section 6 of the paper ("Per-request placement switching") lets every request name a placement,
+// i.e. one mixer per layer, and dispatches inside the layer on that name with no global mutable
+// state; its scheduler still batches same-placement requests together.  Here a batch may mix
+// placements freely: a plan groups the requests per (layer, mixer) once, and every kernel takes
+// the group's request list as an indirection, so a layer costs one launch per mixer present.
+#include <cstring>
+#include <vector>
+
+#include "common.h"
+
+struct sa_plan {
+  int L = 0, B = 0;
+  // counts[l][m] requests run mixer m at layer l; their ids sit at offset[l][m] of the device list.
+  std::vector<int> counts, offsets;
+  int32_t* dev_lists = nullptr;  // L*B ints: per layer the requests grouped by mixer (F,S,K,G)
+};
+
+namespace {
+
+int mixer_index(char c) {
+  switch (c) {
+    case 'F': return 0;
+    case 'S': return 1;
+    case 'K': return 2;
+    case 'G': return 3;
+    default: return -1;
+  }
+}
+
+}  // namespace
+
+extern "C" sa_status placement_plan_create(const char* const* placements, int n_placements, int L,
+                                           const int32_t* placement_id, int B, sa_plan** plan_out) {
+  const char* name = "placement_plan_create";
+  SA_REQUIRE(plan_out, SA_EINVAL, "%s: plan_out is null", name);
+  *plan_out = nullptr;
+  SA_REQUIRE(placements && n_placements >= 1 && L >= 1 && B >= 0, SA_EINVAL, "%s: bad placement table or sizes", name);
+  SA_REQUIRE(B == 0 || placement_id, SA_EINVAL, "%s: placement_id is null", name);
+  for (int i = 0; i < n_placements; ++i) {
+    SA_REQUIRE(placements[i], SA_EINVAL, "%s: placement %d is null", name, i);
+    SA_REQUIRE(static_cast<int>(std::strlen(placements[i])) == L, SA_EINVAL,
+               "%s: placement %d has %zu characters, the stack has %d layers", name, i, std::strlen(placements[i]), L);
+    for (int l = 0; l < L; ++l)
+      SA_REQUIRE(mixer_index(placements[i][l]) >= 0, SA_EINVAL, "%s: placement %d layer %d: unknown mixer '%c'", name,
+                 i, l, placements[i][l]);
+  }
+  for (int r = 0; r < B; ++r)
+    SA_REQUIRE(placement_id[r] >= 0 && placement_id[r] < n_placements, SA_EINVAL,
+               "%s: request %d names placement %d, only %d exist", name, r, placement_id[r], n_placements);
+
+  sa_plan* plan = new sa_plan;
+  plan->L = L;
+  plan->B = B;
+  plan->counts.assign(static_cast<size_t>(L) * 4, 0);
+  plan->offsets.assign(static_cast<size_t>(L) * 4, 0);
+  std::vector<int32_t> lists(static_cast<size_t>(L) * B);
+  for (int l = 0; l < L; ++l) {
+    int at = 0;
+    for (int m = 0; m < 4; ++m) {
+      plan->offsets[l * 4 + m] = l * B + at;
+      for (int r = 0; r < B; ++r)
+        if (mixer_index(placements[placement_id[r]][l]) == m) lists[static_cast<size_t>(l) * B + at++] = r;
+      plan->counts[l * 4 + m] = l * B + at - plan->offsets[l * 4 + m];
+    }
+  }
+  if (!lists.empty()) {
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev_lists), lists.size() * sizeof(int32_t));
+    if (e == hipSuccess)
+      e = hipMemcpy(plan->dev_lists, lists.data(), lists.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      if (plan->dev_lists) (void)hipFree(plan->dev_lists);
+      delete plan;
+      return sa::fail(SA_EHIP, "%s: %s", name, hipGetErrorString(e));
+    }
+  }
+  *plan_out = plan;
+  return SA_OK;
+}
+
+extern "C" void placement_plan_destroy(sa_plan* plan) {
+  if (!plan) return;
+  if (plan->dev_lists) (void)hipFree(plan->dev_lists);
+  delete plan;
+}
+
+extern "C" int placement_plan_count(const sa_plan* plan, int layer, char mixer) {
+  if (!plan || layer < 0 || layer >= plan->L || mixer_index(mixer) < 0) return -1;
+  return plan->counts[layer * 4 + mixer_index(mixer)];
+}
+
+extern "C" size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* sh, int T, int max_seq_len, int window) {
+  if (!plan || !sh) return 0;
+  size_t need = 0;
+  for (int l = 0; l < plan->L; ++l) {
+    const int nf = plan->counts[l * 4 + 0], ns = plan->counts[l * 4 + 1];
+    if (nf) need = std::max(need, attn_decode_workspace_bytes(nf, T, sh->Hq, sh->Hkv, sh->D, max_seq_len, 0));
+    if (ns) need = std::max(need, attn_decode_workspace_bytes(ns, T, sh->Hq, sh->Hkv, sh->D, max_seq_len, window));
+  }
+  return need;
+}
+
+extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* sh, int T, int window,
+                                      float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+  const char* name = "placement_decode";
+  SA_REQUIRE(plan && io && sh, SA_EINVAL, "%s: null plan, io or shapes", name);
+  SA_REQUIRE(window > 0, SA_EINVAL, "%s: the sliding window must be positive (window=%d)", name, window);
+  SA_REQUIRE(static_cast<long long>(sh->H) * sh->dv == static_cast<long long>(sh->Hq) * sh->D, SA_EINVAL,
+             "%s: H*dv must equal Hq*D so that all mixers share the output rows", name);
+  const int B = plan->B;
+  for (int l = 0; l < plan->L; ++l) {
+    const sa_layer_io& x = io[l];
+    for (int m = 0; m < 4; ++m) {
+      const int n = plan->counts[l * 4 + m];
+      if (n == 0) continue;
+      const int32_t* list = plan->dev_lists + plan->offsets[l * 4 + m];
+      sa_status st;
+      if (m == 0 || m == 1) {
+        st = attn_decode(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, list, n, x.out, B,
+                         T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, m == 0 ? 0 : window, attn_scale,
+                         workspace, workspace_bytes, stream);
+      } else if (m == 2) {
+        st = kda_decode_step(x.q, x.k, x.v, x.alpha_vec, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T,
+                             sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, stream);
+      } else {
+        st = gdn_decode_step(x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T,
+                             sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, stream);
+      }
+      if (st != SA_OK) return st;
+    }
+  }
+  return SA_OK;
+}

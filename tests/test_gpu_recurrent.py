@@ -1,0 +1,139 @@
+"""GPU parity of gdn_decode_step / kda_decode_step against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixers as om
+from paper_2604_19877_amd import binding as sa
+from paper_2604_19877_amd import inputs as gen
+from gpu_util import OUT_TOL, STATE_TOL, Guarded, dev, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+FN = {False: (sa.gdn_decode_step, om.gdn_steps), True: (sa.kda_decode_step, om.kda_steps)}
+
+
+def stepwise_inputs(seed, steps, B, T, H, Hk, dk, dv, kda):
+    """Operands for `steps` consecutive calls of T tokens: arrays [steps,B,T,...]."""
+    p = gen.recurrent_inputs(seed, steps * B, T, H, Hk, dk, dv, kda)
+    return {n: a.reshape((steps, B) + a.shape[1:]) for n, a in p.items()}
+
+
+def as_sequence(p, name):
+    """[steps,B,T,...] -> [B,steps*T,...] for the oracle."""
+    a = p[name]
+    a = np.moveaxis(a, 0, 1)
+    return a.reshape((a.shape[0], a.shape[1] * a.shape[2]) + a.shape[3:])
+
+
+def run_gpu(kda, p, state0, B, T, H, Hk, dk, dv, scale):
+    fn = FN[kda][0]
+    steps = p["q"].shape[0]
+    d = {n: dev(a) for n, a in p.items()}
+    state = dev(state0.copy())
+    out = torch.empty((steps, B, T, H, dv), dtype=torch.float32, device="cuda")
+    for s in range(steps):
+        fn(d["q"][s], d["k"][s], d["v"][s], d["alpha"][s], d["beta"][s], state, state, out[s], None, None, 0,
+           B, T, H, Hk, dk, dv, scale, T)
+    torch.cuda.synchronize()
+    o = host(out)
+    o = np.moveaxis(o, 0, 1).reshape(B, steps * T, H, dv)
+    return o, host(state)
+
+
+@pytest.mark.parametrize("kda", [False, True])
+@pytest.mark.parametrize("T", [1, 8])
+def test_config1_256_tokens_from_zero_state(kda, T):
+    """B=2, H=4, dk=dv=64, 256 tokens, zero initial state; fed one token per call and 8 per call."""
+    B, H, dk, dv, n_tok = 2, 4, 64, 64, 256
+    p = stepwise_inputs(1001 + kda, n_tok // T, B, T, H, H, dk, dv, kda)
+    S0 = np.zeros((B, H, dk, dv), dtype=np.float32)
+    scale = dk ** -0.5
+    o, S = run_gpu(kda, p, S0, B, T, H, H, dk, dv, scale)
+    o_ref, S_ref = FN[kda][1](as_sequence(p, "q"), as_sequence(p, "k"), as_sequence(p, "v"), as_sequence(p, "alpha"),
+                              as_sequence(p, "beta"), S0, scale)
+    assert rel_err(o, o_ref) <= OUT_TOL
+    assert rel_err(S, S_ref) <= STATE_TOL
+
+
+@pytest.mark.parametrize("kda,B", [(False, 64), (True, 64), (True, 256)])
+def test_full_shape_256_steps_sampled_tiles(kda, B):
+    """15B-class shape (32 heads, 128x128 fp32 states ~ N(0, 0.02^2)), 256 consecutive steps on the
+    GPU for every tile; the oracle follows a seeded sample of tiles (tiles are independent)."""
+    H, dk, dv = 32, 128, 128
+    steps = 256 if B == 64 else 32
+    p = stepwise_inputs(1002 + kda + B, steps, B, 1, H, H, dk, dv, kda)
+    S0 = gen.recurrent_state(7, B * H, dk, dv).reshape(B, H, dk, dv)
+    scale = dk ** -0.5
+    o, S = run_gpu(kda, p, S0, B, 1, H, H, dk, dv, scale)
+    assert np.isfinite(o).all() and np.isfinite(S).all()
+    rng = np.random.default_rng(5)
+    tiles = [(int(rng.integers(B)), int(rng.integers(H))) for _ in range(48)] + [(0, 0), (B - 1, H - 1)]
+    seq = {n: as_sequence(p, n) for n in p}
+    for (b, h) in tiles:
+        sl = (slice(b, b + 1), slice(None), slice(h, h + 1))
+        o_ref, S_ref = FN[kda][1](seq["q"][sl], seq["k"][sl], seq["v"][sl], seq["alpha"][sl], seq["beta"][sl],
+                                  S0[b:b + 1, h:h + 1], scale)
+        assert rel_err(o[b, :, h], o_ref[0, :, 0]) <= OUT_TOL, (b, h)
+        assert rel_err(S[b, h], S_ref[0, 0]) <= STATE_TOL, (b, h)
+
+
+@pytest.mark.parametrize("kda", [False, True])
+def test_grouped_key_heads_slots_request_lists_and_commit_prefix(kda):
+    """Hk < H, a permuted slot map, a request sub-list, out-of-place state with n_commit < T; rows that
+    are not listed and all guard bands must stay untouched."""
+    fn, ref = FN[kda]
+    B, T, H, Hk, dk, dv = 5, 4, 8, 2, 128, 128
+    p = gen.recurrent_inputs(2001 + kda, B, T, H, Hk, dk, dv, kda)
+    n_slots = 7
+    S0 = gen.recurrent_state(8, n_slots * H, dk, dv, std=0.5).reshape(n_slots, H, dk, dv)
+    slot = np.array([3, 0, 6, 1, 4], dtype=np.int32)
+    req = np.array([4, 1, 2], dtype=np.int32)
+    d = {n: dev(a) for n, a in p.items()}
+    for n_commit in (0, 2, 4):
+        s_in, s_out = Guarded(S0), Guarded(np.full_like(S0, 7.0))
+        out = Guarded(np.full((B, T, H, dv), 9.0, dtype=np.float32))
+        fn(d["q"], d["k"], d["v"], d["alpha"], d["beta"], s_in.ptr(), s_out.ptr(), out.ptr(), dev(slot), dev(req), len(req),
+           B, T, H, Hk, dk, dv, 0.25, n_commit)
+        torch.cuda.synchronize()
+        got_o, got_s = out.read(), s_out.read()
+        assert np.array_equal(s_in.read(), S0)
+        assert s_in.bands_intact() and s_out.bands_intact() and out.bands_intact()
+        o_ref, S_ref = ref(p["q"][req], p["k"][req], p["v"][req], p["alpha"][req], p["beta"][req], S0[slot[req]], 0.25,
+                           n_commit=n_commit)
+        assert rel_err(got_o[req], o_ref) <= OUT_TOL
+        if n_commit == 0:
+            assert np.array_equal(got_s[slot[req]], S0[slot[req]])
+        else:
+            assert rel_err(got_s[slot[req]], S_ref) <= STATE_TOL
+        untouched_rows = [b for b in range(B) if b not in req]
+        assert (got_o[untouched_rows] == 9.0).all()
+        untouched_slots = [s for s in range(n_slots) if s not in slot[req]]
+        assert (got_s[untouched_slots] == 7.0).all()
+
+
+@pytest.mark.parametrize("kda", [False, True])
+def test_identities_on_the_gpu(kda):
+    """alpha = 1, beta = 0 leaves the state bit-identical; a uniform channel gate makes KDA equal GDN
+    bit for bit (same kernel arithmetic)."""
+    fn, _ = FN[kda]
+    B, H, dk, dv = 3, 4, 128, 128
+    p = gen.recurrent_inputs(2003, B, 1, H, H, dk, dv, kda)
+    S0 = gen.recurrent_state(9, B * H, dk, dv, std=1.0).reshape(B, H, dk, dv)
+    d = {n: dev(a) for n, a in p.items()}
+    state = dev(S0.copy())
+    out = torch.empty((B, 1, H, dv), dtype=torch.float32, device="cuda")
+    fn(d["q"], d["k"], d["v"], torch.ones_like(d["alpha"]), torch.zeros_like(d["beta"]), state, state, out, None, None, 0,
+       B, 1, H, H, dk, dv, 1.0, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(state), S0)
+    if kda:
+        g = gen.recurrent_inputs(2003, B, 1, H, H, dk, dv, False)
+        a_vec = np.repeat(g["alpha"][..., None], dk, axis=-1).astype(np.float32)
+        s1, s2 = dev(S0.copy()), dev(S0.copy())
+        o1, o2 = torch.empty_like(out), torch.empty_like(out)
+        dg = {n: dev(a) for n, a in g.items()}
+        sa.gdn_decode_step(dg["q"], dg["k"], dg["v"], dg["alpha"], dg["beta"], s1, s1, o1, None, None, 0, B, 1, H, H, dk, dv, 0.5, 1)
+        sa.kda_decode_step(dg["q"], dg["k"], dg["v"], dev(a_vec), dg["beta"], s2, s2, o2, None, None, 0, B, 1, H, H, dk, dv, 0.5, 1)
+        torch.cuda.synchronize()
+        assert torch.equal(s1, s2) and torch.equal(o1, o2)
