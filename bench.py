@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of the four token mixers at batch 64 on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one new token for each of 64 sequences through one layer of every mixer at the paper's
+15B-class shapes: a GDN step and a KDA step (32 heads, 128x128 fp32 state per head), full GQA
+attention over 32768-token paged bf16 caches, and sliding-window attention (w = 4096) over the same
+caches with context lengths uniform in [8192, 32768].  Inputs are synthetic, seeded and resident in
+HBM before the timed region.  Prints ONE JSON line; `value` is sequences advanced per second through
+that four-mixer layer set, `kernels` gives every kernel's own tokens/s and fraction of the 8 TB/s
+HBM peak, `roofline` is the dominant kernel (the full-attention K/V stream).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+B, H, DK, DV = 64, 32, 128, 128
+HQ, HKV, D, PAGE = 32, 8, 128, 16
+CTX, WINDOW = 32768, 4096
+N_STATE_SETS = 8      # 8 x 128 MiB per recurrent mixer: the working set exceeds the 256 MB last-level cache
+N_RING = 8            # distinct pre-staged operand sets
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run the plain 1 GiB copy kernel 3 times after the timed region (counter calibration)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2604_19877_amd import binding as sa
+    from paper_2604_19877_amd import inputs as gen
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+    # ---------------------------------------------------------------- recurrent operands and states
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1002)
+    rec = {}
+    for name, kda in (("gdn", False), ("kda", True)):
+        ring = [{n: dev(a) for n, a in gen.recurrent_inputs(1002 + 17 * i + kda, B, 1, H, H, DK, DV, kda).items()}
+                for i in range(N_RING)]
+        states = torch.empty((N_STATE_SETS, B * H, DK, DV), dtype=torch.float32, device="cuda")
+        states.normal_(0.0, 0.02, generator=g)
+        out = torch.empty((B, 1, H, DV), dtype=torch.float32, device="cuda")
+        rec[name] = (ring, states, out)
+    rec_scale = DK ** -0.5
+
+    # ---------------------------------------------------------------- paged KV cache
+    max_pages = CTX // PAGE
+    table_h, n_pages = gen.page_table(1004, np.full(B, CTX, dtype=np.int32), max_pages)
+    table = dev(table_h)
+    kpool = torch.empty((n_pages, HKV, PAGE * D), dtype=torch.bfloat16, device="cuda")
+    vpool = torch.empty((n_pages, HKV, PAGE * D), dtype=torch.bfloat16, device="cuda")
+    kpool.normal_(generator=g)
+    vpool.normal_(generator=g)
+    lens_fa_h = np.full(B, CTX, dtype=np.int32)
+    lens_swa_h = gen.context_lengths(1005, B, 8192, CTX)
+    lens_fa, lens_swa = dev(lens_fa_h), dev(lens_swa_h)
+    q_ring_h = [gen.attention_inputs(1006 + i, B, 1, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"] for i in range(N_RING)]
+    q_ring = [dev(q) for q in q_ring_h]
+    attn_scale = D ** -0.5
+    ws_bytes = max(sa.attn_decode_workspace_bytes(B, 1, HQ, HKV, D, CTX, 0),
+                   sa.attn_decode_workspace_bytes(B, 1, HQ, HKV, D, CTX, WINDOW))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    out_fa = torch.empty((B, 1, HQ, D), dtype=torch.float32, device="cuda")
+    out_swa = torch.empty((B, 1, HQ, D), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        for name, fn in (("gdn", sa.gdn_decode_step), ("kda", sa.kda_decode_step)):
+            ring, states, out = rec[name]
+            x, s = ring[i % N_RING], states[i % N_STATE_SETS]
+            fn(x["q"], x["k"], x["v"], x["alpha"], x["beta"], s, s, out, None, None, 0, B, 1, H, H, DK, DV, rec_scale, 1,
+               stream)
+        q = q_ring[i % N_RING]
+        sa.attn_decode(q, kpool, vpool, n_pages, table, max_pages, lens_fa, None, 0, out_fa, B, 1, HQ, HKV, D, PAGE, CTX, 0,
+                       attn_scale, ws, ws_bytes, stream)
+        sa.attn_decode(q, kpool, vpool, n_pages, table, max_pages, lens_swa, None, 0, out_swa, B, 1, HQ, HKV, D, PAGE, CTX,
+                       WINDOW, attn_scale, ws, ws_bytes, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    sa.sa_prof_enable(True)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sa.sa_prof_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    copy_entry = None
+    if args.copy_calibration:
+        n_copy = 1 << 30
+        src = torch.empty(n_copy, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(n_copy, dtype=torch.uint8, device="cuda")
+        src.random_(0, 255, generator=g)
+        sa.sa_prof_enable(True)
+        for _ in range(3):
+            sa.sa_copy_bytes(src, dst, n_copy, stream)
+        torch.cuda.synchronize()
+        sa.sa_prof_enable(False)
+        _, _, copy_ms = sa.sa_prof_read(sa.SA_K_COPY, 8)
+        avg = sum(copy_ms) / len(copy_ms)
+        copy_entry = {"avg_us": round(avg * 1e3, 2), "bytes_read_plus_written": 2 * n_copy,
+                      "GBps": round(2 * n_copy / (avg * 1e-3) / 1e9, 1)}
+
+    # ---------------------------------------------------------------- per-kernel durations (HIP events)
+    cap = 2 * args.steps + 8
+    _, _, gdn_ms = sa.sa_prof_read(sa.SA_K_GDN, cap)
+    _, _, kda_ms = sa.sa_prof_read(sa.SA_K_KDA, cap)
+    _, _, split_ms = sa.sa_prof_read(sa.SA_K_ATTN_SPLIT, cap)
+    _, _, merge_ms = sa.sa_prof_read(sa.SA_K_ATTN_MERGE, cap)
+    fa_ms, swa_ms = split_ms[0::2], split_ms[1::2]          # launch order within a step: FA, then SWA
+    fa_merge_ms, swa_merge_ms = merge_ms[0::2], merge_ms[1::2]
+
+    state_bytes = 2 * B * H * DK * DV * 4
+    rec_operands = B * (2 * H * DK * 2 + H * DV * 2 + H * DV * 4 + H * 4)     # q,k,v bf16, out fp32, beta
+    alg = {
+        "gdn_decode_step": state_bytes + rec_operands + B * H * 4,
+        "kda_decode_step": state_bytes + rec_operands + B * H * DK * 4,
+        "attn_split_fa": int(lens_fa_h.astype(np.int64).sum()) * 2 * HKV * D * 2,
+        "attn_split_swa": int(np.minimum(lens_swa_h, WINDOW).astype(np.int64).sum()) * 2 * HKV * D * 2,
+    }
+
+    def entry(ms_list, nbytes):
+        avg = sum(ms_list) / max(len(ms_list), 1)
+        gbs = nbytes / (avg * 1e-3) / 1e9 if avg > 0 else 0.0
+        return {"avg_us": round(avg * 1e3, 2), "min_us": round(min(ms_list) * 1e3, 2) if ms_list else None,
+                "launches": len(ms_list), "alg_bytes": nbytes, "GBps": round(gbs, 1),
+                "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "tokens_per_s": round(B / (avg * 1e-3), 1) if avg > 0 else None}
+
+    kernels = {
+        "gdn_decode_step": entry(gdn_ms, alg["gdn_decode_step"]),
+        "kda_decode_step": entry(kda_ms, alg["kda_decode_step"]),
+        "attn_split_fa": entry(fa_ms, alg["attn_split_fa"]),
+        "attn_split_swa": entry(swa_ms, alg["attn_split_swa"]),
+        "attn_merge_fa": {"avg_us": round(sum(fa_merge_ms) / max(len(fa_merge_ms), 1) * 1e3, 2)},
+        "attn_merge_swa": {"avg_us": round(sum(swa_merge_ms) / max(len(swa_merge_ms), 1) * 1e3, 2)},
+    }
+    if copy_entry:
+        kernels["copy_1GiB"] = copy_entry
+    dom = kernels["attn_split_fa"]
+    roofline = {"kernel": "attn_split_kernel (full attention, 64 x 32768 tokens)", "bound": "hbm",
+                "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_hbm_peak"],
+                "traffic": None}
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(np, torch, gen, rec, q_ring_h[0], kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale,
+                           attn_scale)
+
+    line = {
+        "metric": "mixer decode tokens/s at batch 64 + % of MI355X peak HBM GB/s",
+        "value": round(B / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32 (bf16 operands and KV cache)",
+        "data": "synthetic",
+        "config": {"workload": "batch-64 decode step through one GDN, one KDA, one FA (32768-token contexts) and one SWA "
+                               "(w=4096, contexts U[8192,32768]) layer; 32 heads, 128x128 fp32 states, 32q/8kv heads, "
+                               "head dim 128, 16-token pages, shuffled page table",
+                   "batch": B, "state_sets_rotated": N_STATE_SETS},
+        "hbm_frac_by_kernel": {k: v["frac_hbm_peak"] for k, v in kernels.items() if "frac_hbm_peak" in v},
+        "kernels": kernels,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(np, torch, gen, rec, q_h, kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale, attn_scale):
+    """Times the fp64 oracle, as it stands, on a sample of the same step and scales to the full step."""
+    from oracle import kv_layout as kl
+    from oracle import mixers as om
+
+    n_seq, n_groups = 64, 64
+    t_rec = {}
+    for name, kda, fn in (("gdn", False, om.gdn_steps), ("kda", True, om.kda_steps)):
+        p = gen.recurrent_inputs(1002 + kda, B, 1, H, H, DK, DV, kda)
+        S0 = rec[name][1][0].view(B, H, DK, DV)[:n_seq].cpu().numpy()
+        t = time.perf_counter()
+        fn(p["q"][:n_seq], p["k"][:n_seq], p["v"][:n_seq], p["alpha"][:n_seq], p["beta"][:n_seq], S0, rec_scale)
+        t_rec[name] = (time.perf_counter() - t) * (B / n_seq)
+    t_attn = {}
+    tbl = torch.from_numpy(table_h).cuda()
+    rng = np.random.default_rng(77)
+    for name, lens, window in (("fa", lens_fa_h, 0), ("swa", lens_swa_h, WINDOW)):
+        total = 0.0
+        for _ in range(n_groups):
+            b, grp = int(rng.integers(B)), int(rng.integers(HKV))
+            L = int(lens[b])
+            pages = tbl[b, :(L + PAGE - 1) // PAGE].long()
+            kph = kpool[pages, grp].view(torch.int16).cpu().numpy().view(np.uint16)[:, None]
+            vph = vpool[pages, grp].view(torch.int16).cpu().numpy().view(np.uint16)[:, None]
+            klog, vlog = kl.to_logical(kph, vph, D)
+            ident = np.arange(len(pages), dtype=np.int32)[None]
+            heads = slice(grp * (HQ // HKV), (grp + 1) * (HQ // HKV))
+            qs = q_h[b:b + 1, :, heads]
+            t = time.perf_counter()
+            om.attn_decode(qs, klog, vlog, ident, [L], window, attn_scale)   # 4 query heads on one KV head
+            total += time.perf_counter() - t
+        t_attn[name] = total * (B * HKV / n_groups)
+    t_step = t_rec["gdn"] + t_rec["kda"] + t_attn["fa"] + t_attn["swa"]
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    return {"value": round(B / t_step, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "host_cores_available": len(os.sched_getaffinity(0)),
+            "sample": "numpy fp64 oracle timed on %d of 64 sequences (all 32 heads) for one GDN and one KDA step and on "
+                      "%d of 512 (sequence, KV head) groups (4 query heads each) for FA and for SWA, each scaled to the "
+                      "full step; einsum parts run on one thread, matrix-vector products on the BLAS threads counted "
+                      "in `cores`" % (n_seq, n_groups),
+            "seconds_per_full_step_extrapolated": round(t_step, 2)}
+
+
+if __name__ == "__main__":
+    main()

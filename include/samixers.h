@@ -172,8 +172,10 @@ sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_
 enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5, SA_K_COUNT = 6 };
 /* While enabled, every launch of the kernels above is bracketed by HIP events on its stream. */
 void sa_prof_enable(int on);
-/* Waits for the recorded events of `kernel`, returns their count and summed duration, and forgets them. */
-sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms);
+/* Waits for the recorded events of `kernel`, returns their count and summed duration, and forgets them.
+ * If ms_each is not NULL (host array of `capacity` floats) the first `capacity` durations are
+ * also stored there in launch order. */
+sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms, float* ms_each, int capacity);
 /* Plain streaming copy of n_bytes (multiple of 16) used to calibrate bandwidth counters. */
 sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, void* stream);
 

@@ -55,7 +55,7 @@ _SIGNATURES = {
     "placement_decode": (c_int, [c_void_p, ctypes.POINTER(sa_layer_io), ctypes.POINTER(sa_shapes), c_int, c_int, c_float,
                                  c_float, c_void_p, c_size_t, c_void_p]),
     "sa_prof_enable": (None, [c_int]),
-    "sa_prof_read": (c_int, [c_int, ctypes.POINTER(c_int), ctypes.POINTER(c_float)]),
+    "sa_prof_read": (c_int, [c_int, ctypes.POINTER(c_int), ctypes.POINTER(c_float), ctypes.POINTER(c_float), c_int]),
     "sa_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -192,9 +192,13 @@ def sa_prof_enable(on):
     lib().sa_prof_enable(int(bool(on)))
 
 
-def sa_prof_read(kernel):
+def sa_prof_read(kernel, capacity=0):
+    """Returns (n_launches, total_ms) or, with capacity > 0, (n_launches, total_ms, [ms of each launch])."""
     n, ms = c_int(0), c_float(0.0)
-    _check(lib().sa_prof_read(kernel, ctypes.byref(n), ctypes.byref(ms)))
+    each = (c_float * capacity)() if capacity > 0 else None
+    _check(lib().sa_prof_read(kernel, ctypes.byref(n), ctypes.byref(ms), each, capacity))
+    if capacity > 0:
+        return n.value, ms.value, list(each)[:min(n.value, capacity)]
     return n.value, ms.value
 
 

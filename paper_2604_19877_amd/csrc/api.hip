@@ -59,7 +59,7 @@ int sa_version(void) { return 100; }
 
 void sa_prof_enable(int on) { g_prof_on = on != 0; }
 
-sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms) {
+sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms, float* ms_each, int capacity) {
   SA_REQUIRE(kernel >= 0 && kernel < SA_K_COUNT, SA_EINVAL, "sa_prof_read: unknown kernel id %d", kernel);
   SA_REQUIRE(n_launches && total_ms, SA_EINVAL, "sa_prof_read: null output pointer");
   std::vector<EventPair> taken;
@@ -69,12 +69,15 @@ sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms) {
   }
   float sum = 0.f;
   sa_status st = SA_OK;
+  int at = 0;
   for (const EventPair& p : taken) {
     float ms = 0.f;
     hipError_t e = hipEventSynchronize(p.stop);
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.start, p.stop);
     if (e != hipSuccess) st = sa::fail(SA_EHIP, "sa_prof_read: %s", hipGetErrorString(e));
     sum += ms;
+    if (ms_each && at < capacity) ms_each[at] = ms;
+    ++at;
     (void)hipEventDestroy(p.start);
     (void)hipEventDestroy(p.stop);
   }
