@@ -1,0 +1,114 @@
+"""GPU parity of placement_decode against the oracle: a 48-layer mixers-only stack, three seeded
+placements of 12 FA / 12 SWA / 12 KDA / 12 GDN layers, a different placement per request."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_layout as kl
+from oracle import mixers as om
+from paper_2604_19877_amd import binding as sa
+from paper_2604_19877_amd import inputs as gen
+from gpu_util import OUT_TOL, STATE_TOL, dev, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+H, DK, DV, HQ, HKV, D = 32, 128, 128, 32, 8, 128
+
+
+def build_stack(seed, L, B, T, ctx, max_pages):
+    """Host-side operands of every layer for the whole batch (each layer has its own)."""
+    lens = np.full(B, ctx, dtype=np.int32)
+    layers = []
+    for l in range(L):
+        r = gen.recurrent_inputs(seed + 10 * l, B, T, H, H, DK, DV, False)
+        rv = gen.recurrent_inputs(seed + 10 * l + 1, B, T, H, H, DK, DV, True)
+        a = gen.attention_inputs(seed + 10 * l + 2, B, T, HQ, HKV, D, lens, max_pages)
+        klog, vlog = gen.logical_pools(a["k_tok"], a["v_tok"], a["page_table"], lens, a["n_pages"])
+        state = gen.recurrent_state(seed + 10 * l + 3, B * H, DK, DV).reshape(B, H, DK, DV)
+        layers.append({"q": r["q"], "k": r["k"], "v": r["v"], "alpha_scalar": r["alpha"], "alpha_vec": rv["alpha"],
+                       "beta": r["beta"], "state": state, "qa": a["q"], "kpool": klog, "vpool": vlog,
+                       "page_table": a["page_table"], "seq_lens": lens, "n_pages": a["n_pages"]})
+    return layers
+
+
+@pytest.mark.parametrize("T", [1, 4])
+def test_48_layer_stack_three_placements(T):
+    L, B, ctx, window, max_pages = 48, 6, 1024, 256, 64
+    placements = [gen.placement_string(5001 + i, L) for i in range(3)]
+    pid = np.arange(B, dtype=np.int32) % 3
+    layers = build_stack(5100 + T, L, B, T, ctx, max_pages)
+    attn_scale, rec_scale = D ** -0.5, DK ** -0.5
+
+    plan = sa.placement_plan_create(placements, pid)
+    try:
+        for l in range(L):
+            counts = {m: sa.placement_plan_count(plan, l, m) for m in "FSKG"}
+            assert sum(counts.values()) == B
+            for m in "FSKG":
+                assert counts[m] == sum(placements[p][l] == m for p in pid)
+        shapes = sa.sa_shapes(H, H, DK, DV, HQ, HKV, D, 16)
+        ws_bytes = sa.placement_workspace_bytes(plan, shapes, T, ctx, window)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+        keep, ios, outs, states = [], [], [], []
+        for io in layers:
+            kphys, vphys = kl.to_physical(io["kpool"], io["vpool"])
+            t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
+            t["state"] = dev(io["state"].copy())
+            t["kpool"], t["vpool"] = dev(kphys), dev(vphys)
+            t["out"] = torch.full((B, T, H, DV), 55.0, dtype=torch.float32, device="cuda")
+            keep.append(t)
+            outs.append(t["out"])
+            states.append(t["state"])
+            ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"], alpha_vec=t["alpha_vec"],
+                                        beta=t["beta"], state=t["state"], slot_idx=None, q_attn=t["qa"], kpool=t["kpool"],
+                                        vpool=t["vpool"], n_pages=io["n_pages"], page_table=t["page_table"],
+                                        seq_lens=t["seq_lens"], max_pages=max_pages, max_seq_len=ctx, out=t["out"]))
+        sa.placement_decode(plan, ios, shapes, T, window, attn_scale, rec_scale, ws, ws_bytes)
+        torch.cuda.synchronize()
+    finally:
+        sa.placement_plan_destroy(plan)
+
+    ref_outs, ref_states = om.placement_decode(placements, pid, layers, window, attn_scale, rec_scale)
+    for l in range(L):
+        got_o, got_s = host(outs[l]), host(states[l])
+        assert np.isfinite(got_o).all()
+        for r in range(B):
+            m = placements[pid[r]][l]
+            assert rel_err(got_o[r], ref_outs[l][r]) <= OUT_TOL, (l, r, m)
+            if m in "KG":
+                assert rel_err(got_s[r], ref_states[l][r]) <= STATE_TOL, (l, r, m)
+            else:
+                assert np.array_equal(got_s[r], layers[l]["state"][r]), (l, r, m)   # attention rows leave the state alone
+
+
+def test_same_placement_for_all_requests_and_empty_batch():
+    """All requests on one placement: every layer is a single launch over the whole batch."""
+    L, B, ctx, window, max_pages = 4, 3, 200, 64, 16
+    layers = build_stack(5200, L, B, 1, ctx, max_pages)
+    placements = ["FKSG", "GGGG"]
+    pid = np.zeros(B, dtype=np.int32)
+    plan = sa.placement_plan_create(placements, pid)
+    shapes = sa.sa_shapes(H, H, DK, DV, HQ, HKV, D, 16)
+    ws_bytes = sa.placement_workspace_bytes(plan, shapes, 1, ctx, window)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    keep, ios = [], []
+    for io in layers:
+        kphys, vphys = kl.to_physical(io["kpool"], io["vpool"])
+        t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
+        t["state"], t["kpool"], t["vpool"] = dev(io["state"].copy()), dev(kphys), dev(vphys)
+        t["out"] = torch.zeros((B, 1, H, DV), dtype=torch.float32, device="cuda")
+        keep.append(t)
+        ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"], alpha_vec=t["alpha_vec"],
+                                    beta=t["beta"], state=t["state"], q_attn=t["qa"], kpool=t["kpool"], vpool=t["vpool"],
+                                    n_pages=io["n_pages"], page_table=t["page_table"], seq_lens=t["seq_lens"],
+                                    max_pages=max_pages, max_seq_len=ctx, out=t["out"]))
+    sa.placement_decode(plan, ios, shapes, 1, window, D ** -0.5, DK ** -0.5, ws, ws_bytes)
+    torch.cuda.synchronize()
+    sa.placement_plan_destroy(plan)
+    ref_outs, _ = om.placement_decode(placements, pid, layers, window, D ** -0.5, DK ** -0.5)
+    for l in range(L):
+        assert rel_err(host(keep[l]["out"]), ref_outs[l]) <= OUT_TOL
+    empty = sa.placement_plan_create(placements, [])
+    assert sa.placement_plan_count(empty, 0, "F") == 0
+    sa.placement_decode(empty, ios, shapes, 1, window, 1.0, 1.0, ws, ws_bytes)
+    sa.placement_plan_destroy(empty)
