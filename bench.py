@@ -29,6 +29,9 @@ HQ, HKV, D, PAGE = 32, 8, 128, 16
 CTX, WINDOW = 32768, 4096
 N_STATE_SETS = 8      # 8 x 128 MiB per recurrent mixer: the working set exceeds the 256 MB last-level cache
 N_RING = 8            # distinct pre-staged operand sets
+# HBM bytes per launch of the full-attention split kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by the copy-kernel calibration (profiles/batch64_step_all_kernels_hbm_bytes.txt).
+FA_SPLIT_TRAFFIC_BYTES = 8603409408
 
 
 def parse_args():
@@ -37,6 +40,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
+    ap.add_argument("--no-placement", action="store_true", help="skip the 48-layer placement stack at batch 128")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the plain 1 GiB copy kernel 3 times after the timed region (counter calibration)")
     return ap.parse_args()
@@ -173,13 +177,20 @@ def main():
     dom = kernels["attn_split_fa"]
     roofline = {"kernel": "attn_split_kernel (full attention, 64 x 32768 tokens)", "bound": "hbm",
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_hbm_peak"],
-                "traffic": None}
+                "traffic": FA_SPLIT_TRAFFIC_BYTES}
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(np, torch, gen, rec, q_ring_h[0], kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale,
                            attn_scale)
+
+    # ---------------------------------------------------------------- 48-layer placement stack (batch 128)
+    placement = None
+    if not args.no_placement:
+        del kpool, vpool, rec
+        torch.cuda.empty_cache()
+        placement = placement_stack(torch, sa, stream)
 
     line = {
         "metric": "mixer decode tokens/s at batch 64 + % of MI355X peak HBM GB/s",
@@ -195,8 +206,34 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "placement48": placement,
     }
     print(json.dumps(line))
+
+
+def placement_stack(torch, sa, stream, steps=8, warmup=2):
+    """One decode step of the 48-layer mixers-only stack at batch 128, 16384-token contexts, three
+    placements of 12 FA / 12 SWA / 12 KDA / 12 GDN layers assigned per request."""
+    from paper_2604_19877_amd.workloads import PlacementWorkload
+    w = PlacementWorkload(B=128, L=48, ctx=16384, window=WINDOW, T=1, seed=5000)
+    try:
+        for _ in range(warmup):
+            w.step(stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            w.step(stream)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        nbytes = w.algorithmic_bytes()
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        return {"workload": "48-layer mixers-only stack, batch 128, contexts 16384, 3 placements (12 FA/12 SWA/12 KDA/12 GDN "
+                            "each) assigned per request, one global paged KV pool, bounded SWA caches",
+                "ms_per_step": round(ms, 3), "tokens_per_s": round(w.B / (ms * 1e-3), 1), "steps": steps,
+                "alg_bytes": nbytes, "GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                "kv_pool_GiB": round(2 * w.n_pages * HKV * PAGE * D * 2 / 2 ** 30, 1)}
+    finally:
+        w.close()
 
 
 def cpu_baseline(np, torch, gen, rec, q_h, kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale, attn_scale):
