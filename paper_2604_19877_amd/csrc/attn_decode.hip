@@ -21,6 +21,8 @@
 // keeps that same row in the lane, so the whole online softmax is lane-local except for a 2-step
 // maximum over the 4 token groups.  Probabilities are split into two bf16 terms (p = hi + lo) so the
 // second product carries ~16 mantissa bits of p instead of 8.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace {
@@ -66,7 +68,13 @@ SplitPlan plan_splits(int n_req, int Hkv, int T, int max_seq_len, int window) {
     if (span < max_pages) max_pages = span;
   }
   if (max_pages < 1) max_pages = 1;
-  const long long target_groups = 4096;  // workgroups wanted in flight over the whole launch
+  // Workgroups wanted over the whole launch (16 per CU).  SAMIXERS_ATTN_TARGET_GROUPS overrides it
+  // for tuning runs; it is read once.
+  static const long long target_groups = [] {
+    const char* e = std::getenv("SAMIXERS_ATTN_TARGET_GROUPS");
+    long long v = e ? std::atoll(e) : 0;
+    return v > 0 ? v : 4096LL;
+  }();
   long long pairs = static_cast<long long>(n_req) * Hkv;
   long long want = (target_groups + pairs - 1) / pairs;
   long long most = (max_pages + 7) / 8;  // at least 8 pages (2 per wavefront) per range

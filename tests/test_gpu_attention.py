@@ -15,7 +15,7 @@ HQ, HKV, D = 32, 8, 128
 SCALE = D ** -0.5
 
 
-def gpu_attention(q, kphys, vphys, table, lens, T, window, max_seq_len, req=None, n_pages=None):
+def gpu_attention(q, kphys, vphys, table, lens, T, window, max_seq_len, req=None, n_pages=None, HQ=HQ, HKV=HKV):
     """kphys/vphys: device tensors or host uint16 arrays [n_pages,Hkv,2048]."""
     B = len(lens)
     kd = kphys if torch.is_tensor(kphys) else dev(kphys)
@@ -138,6 +138,19 @@ def test_append_then_attend_round_trip():
         klog, vlog = gen.logical_pools(p["k_tok"], p["v_tok"], p["page_table"], cur + 1, p["n_pages"])
         ref = om.attn_decode(p["q"], klog, vlog, p["page_table"], cur + 1, 0, SCALE)
         assert rel_err(got, ref) <= OUT_TOL
+
+
+@pytest.mark.parametrize("hq,hkv,T", [(8, 8, 1), (8, 8, 8), (16, 8, 2), (24, 8, 3), (32, 4, 2), (16, 1, 1), (5, 5, 3)])
+def test_other_head_groupings_and_token_counts(hq, hkv, T):
+    """Group sizes 1..16 and 1..8 new tokens (up to 16 query rows per KV head), windowed and full."""
+    lens = np.array([T + 3, 70, 555, 1300], dtype=np.int32)
+    p = gen.attention_inputs(3060 + hq + T, len(lens), T, hq, hkv, D, lens, 96)
+    klog, vlog = gen.logical_pools(p["k_tok"], p["v_tok"], p["page_table"], lens, p["n_pages"])
+    kphys, vphys = kl.to_physical(klog, vlog)
+    for window in (0, 200):
+        got = gpu_attention(p["q"], kphys, vphys, p["page_table"], lens, T, window, 1536, HQ=hq, HKV=hkv)
+        ref = om.attn_decode(p["q"], klog, vlog, p["page_table"], lens, window, SCALE)
+        assert rel_err(got, ref) <= OUT_TOL, window
 
 
 def _device_pools(seed, n_pages):
