@@ -32,10 +32,17 @@ constexpr int kD = 128;
 constexpr int kBlockElems = kPage * kD;  // bf16 elements of one (page, head) K or V block
 constexpr int kWaves = 4;
 constexpr float kNegBig = -1.0e30f;
+// Dynamic LDS requested on top of the 32.5 KiB the split kernel uses, so that only 2 workgroups fit
+// in a CU's 160 KiB.  With 3 resident workgroups the same kernel streams 2-3 % slower and with 4
+// (forced by a register cap) 5-15 % slower: more concurrent page streams than that only add
+// contention in the memory system.
+constexpr int kOccupancyPadBytes = 24 * 1024;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 struct AttnParams {
   const uint16_t* q;
@@ -68,13 +75,17 @@ SplitPlan plan_splits(int n_req, int Hkv, int T, int max_seq_len, int window) {
     if (span < max_pages) max_pages = span;
   }
   if (max_pages < 1) max_pages = 1;
-  // Workgroups wanted over the whole launch (16 per CU).  SAMIXERS_ATTN_TARGET_GROUPS overrides it
-  // for tuning runs; it is read once.
-  static const long long target_groups = [] {
+  // Workgroups wanted over the whole launch.  Measured on MI355X: the K/V stream runs fastest with
+  // 2 workgroups (8 wavefronts) per CU and long page ranges; more, shorter ranges only pay when
+  // sequence lengths are ragged (full attention), where they even out the load.  A window bounds
+  // every sequence's work equally, so one or two ranges per (request, KV head) are enough.
+  // SAMIXERS_ATTN_TARGET_GROUPS overrides the choice for tuning runs; it is read once.
+  static const long long forced = [] {
     const char* e = std::getenv("SAMIXERS_ATTN_TARGET_GROUPS");
     long long v = e ? std::atoll(e) : 0;
-    return v > 0 ? v : 4096LL;
+    return v > 0 ? v : 0LL;
   }();
+  const long long target_groups = forced ? forced : (window > 0 ? 512 : 2048);
   long long pairs = static_cast<long long>(n_req) * Hkv;
   long long want = (target_groups + pairs - 1) / pairs;
   long long most = (max_pages + 7) / 8;  // at least 8 pages (2 per wavefront) per range
@@ -106,10 +117,17 @@ __device__ __forceinline__ void load_page(PageFrags& f, const uint16_t* kpool, c
   const size_t block = (static_cast<size_t>(phys) * Hkv + g) * kBlockElems;
   const uint16_t* kb = kpool + block + lane * 8;
   const uint16_t* vb = vpool + block + lane * 4;
+  // every K and V byte is read once per step: non-temporal loads
 #pragma unroll
-  for (int i = 0; i < 4; ++i) f.k[i] = *reinterpret_cast<const uint4*>(kb + i * 512);
+  for (int i = 0; i < 4; ++i) {
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + i * 512));
+    f.k[i] = uint4{t[0], t[1], t[2], t[3]};
+  }
 #pragma unroll
-  for (int nb = 0; nb < 8; ++nb) f.v[nb] = *reinterpret_cast<const uint2*>(vb + nb * 256);
+  for (int nb = 0; nb < 8; ++nb) {
+    const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(vb + nb * 256));
+    f.v[nb] = uint2{t[0], t[1]};
+  }
 }
 
 __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
@@ -117,7 +135,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
   __shared__ float sm_m[kWaves][16];
   __shared__ float sm_l[kWaves][16];
 
-  const int split = blockIdx.x, g = blockIdx.y, r = blockIdx.z;
+  // KV head fastest: consecutive workgroups go to consecutive XCDs, and every KV head carries the
+  // same amount of work, whereas page ranges do not (late ranges only exist for long sequences).
+  const int g = blockIdx.x, split = blockIdx.y, r = blockIdx.z;
   const int b = p.req_idx ? p.req_idx[r] : r;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -273,8 +293,14 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
       l = fmaf(sm_l[w][rr], f, l);
       acc = fmaf(sm_o[w][rr][d], f, acc);
     }
-    p.part_o[(part + rr) * kD + d] = acc;
-    if (d == 0) p.part_ml[part + rr] = float2{m, l};
+    if (p.nsplit == 1) {
+      // The only range of this (request, KV head): finish here, no partials, no merge kernel.
+      const int t = rr / p.G, hq = g * p.G + rr % p.G;
+      p.out[((static_cast<size_t>(b) * p.T + t) * p.Hq + hq) * kD + d] = l > 0.f ? acc / l : 0.f;
+    } else {
+      p.part_o[(part + rr) * kD + d] = acc;
+      if (d == 0) p.part_ml[part + rr] = float2{m, l};
+    }
   }
 }
 
@@ -395,10 +421,10 @@ extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* v
   hipStream_t s = static_cast<hipStream_t>(stream);
   {
     sa::ProfScope prof(SA_K_ATTN_SPLIT, s);
-    attn_split_kernel<<<dim3(sp.nsplit, Hkv, rows), dim3(256), 0, s>>>(p);
+    attn_split_kernel<<<dim3(Hkv, sp.nsplit, rows), dim3(256), kOccupancyPadBytes, s>>>(p);
   }
   sa_status st = sa::check_launch("attn_decode (split kernel)");
-  if (st != SA_OK) return st;
+  if (st != SA_OK || sp.nsplit == 1) return st;
   {
     sa::ProfScope prof(SA_K_ATTN_MERGE, s);
     attn_merge_kernel<<<dim3(static_cast<unsigned>(rows * Hkv * R)), dim3(128), 0, s>>>(p);

@@ -33,6 +33,30 @@ struct DeltaParams {
   int n_commit;
 };
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// The state is touched exactly once per step, so it is loaded and stored with the non-temporal
+// hint: measured back to back over 1 GiB of states on MI355X this is ~14 % faster than plain
+// accesses, and a whole decode step (GDN, KDA, FA, SWA in turn) ~1 % faster.  Plain accesses only
+// win when the same 128 MiB of state is stepped again while it still sits in the 256 MB last-level
+// cache, which a model with dozens of recurrent layers never does.
+__device__ __forceinline__ float4 load_state(const float* p) {
+  const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return float4{t[0], t[1], t[2], t[3]};
+}
+__device__ __forceinline__ void store_state(float* p, const float4& v) {
+  const f32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
+}
+
+// A per-(row, head) scalar read through the constant address space: the index is the same for the
+// whole workgroup, so this becomes a scalar-cache load instead of 64 identical vector loads.  The
+// gates are inputs and are not written while the kernel runs.
+typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+__device__ __forceinline__ float load_uniform(const float* p, size_t i) {
+  return reinterpret_cast<const_f32_ptr>(reinterpret_cast<uintptr_t>(p))[i];
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -44,24 +68,55 @@ __device__ __forceinline__ float reduce_r8(float x) {
   return x;
 }
 
-template <int N>
-__device__ __forceinline__ void load_bf16_row(const uint16_t* p, float (&dst)[N]) {
-  static_assert(N % 8 == 0, "rows per lane must be a multiple of 8");
+// Operands of one step as they arrive from memory (bf16 still packed).
+template <int RPL, bool KDA>
+struct StepOperands {
+  uint4 k[RPL / 8], q[RPL / 8];
+  float4 alpha_vec[KDA ? RPL / 4 : 1];
+  float alpha, beta;
+  uint2 v;
+};
+
+template <int DK, int DV, bool KDA>
+__device__ __forceinline__ void load_operands(StepOperands<DK / 8, KDA>& o, const DeltaParams& p, size_t bt, int h, int hk,
+                                              int row0, int col0) {
+  constexpr int RPL = DK / 8;
+  const uint4* kp = reinterpret_cast<const uint4*>(p.k + (bt * p.Hk + hk) * DK + row0);
+  const uint4* qp = reinterpret_cast<const uint4*>(p.q + (bt * p.Hk + hk) * DK + row0);
 #pragma unroll
-  for (int i = 0; i < N / 8; ++i) {
-    uint4 w = reinterpret_cast<const uint4*>(p)[i];
-    dst[8 * i + 0] = bf16_lo(w.x);
-    dst[8 * i + 1] = bf16_hi(w.x);
-    dst[8 * i + 2] = bf16_lo(w.y);
-    dst[8 * i + 3] = bf16_hi(w.y);
-    dst[8 * i + 4] = bf16_lo(w.z);
-    dst[8 * i + 5] = bf16_hi(w.z);
-    dst[8 * i + 6] = bf16_lo(w.w);
-    dst[8 * i + 7] = bf16_hi(w.w);
+  for (int i = 0; i < RPL / 8; ++i) {
+    o.k[i] = kp[i];
+    o.q[i] = qp[i];
+  }
+  o.v = *reinterpret_cast<const uint2*>(p.v + (bt * p.H + h) * DV + col0);
+  o.beta = load_uniform(p.beta, bt * p.H + h);
+  if constexpr (KDA) {
+    const float4* ap = reinterpret_cast<const float4*>(p.alpha + (bt * p.H + h) * DK + row0);
+#pragma unroll
+    for (int i = 0; i < RPL / 4; ++i) o.alpha_vec[i] = ap[i];
+    o.alpha = 1.f;
+  } else {
+    o.alpha = load_uniform(p.alpha, bt * p.H + h);
   }
 }
 
-template <int DK, int DV, bool KDA>
+template <int N>
+__device__ __forceinline__ void unpack_bf16(const uint4 (&src)[N / 8], float (&dst)[N]) {
+#pragma unroll
+  for (int i = 0; i < N / 8; ++i) {
+    const uint32_t w[4] = {src[i].x, src[i].y, src[i].z, src[i].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      dst[8 * i + 2 * e] = bf16_lo(w[e]);
+      dst[8 * i + 2 * e + 1] = bf16_hi(w[e]);
+    }
+  }
+}
+
+// MULTI = false: exactly one committed step (T == 1, n_commit == 1), the decode hot path, with an
+// unconditional store.  MULTI = true: any T and n_commit with the tile held in registers; the
+// operands of step t+1 are requested before step t is computed.
+template <int DK, int DV, bool KDA, bool MULTI>
 __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
   constexpr int RPL = DK / 8;  // rows per lane
   const int r = blockIdx.x / p.H;
@@ -74,33 +129,42 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
   const int c8 = lane & 7, r8 = lane >> 3;
   const int row0 = r8 * RPL;
   const int col0 = wave * 32 + c8 * 4;
+  const int T = MULTI ? p.T : 1;
 
   const size_t tile = (static_cast<size_t>(slot) * p.H + h) * (DK * DV);
   const float* sin = p.state_in + tile + static_cast<size_t>(row0) * DV + col0;
   float* sout = p.state_out + tile + static_cast<size_t>(row0) * DV + col0;
 
+  // All requests first: the small operands of step 0, then the 16 state rows of this lane.  The
+  // scheduling barrier keeps the compiler from sinking any of them towards its first use, which
+  // would put a full memory latency on the critical path of every tile.
+  StepOperands<RPL, KDA> cur, nxt;
+  load_operands<DK, DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0);
   float4 s[RPL];
 #pragma unroll
-  for (int m = 0; m < RPL; ++m) s[m] = *reinterpret_cast<const float4*>(sin + m * DV);
+  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + m * DV);
+  __builtin_amdgcn_sched_barrier(0);
 
-  if (p.n_commit == 0 && p.state_out != p.state_in) {
+  if (MULTI && p.n_commit == 0 && p.state_out != p.state_in) {
 #pragma unroll
-    for (int m = 0; m < RPL; ++m) *reinterpret_cast<float4*>(sout + m * DV) = s[m];
+    for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
   }
 
-  for (int t = 0; t < p.T; ++t) {
-    const size_t bt = static_cast<size_t>(b) * p.T + t;
+  for (int t = 0; t < T; ++t) {
+    const size_t bt = static_cast<size_t>(b) * T + t;
+    if constexpr (MULTI) {
+      if (t + 1 < T) load_operands<DK, DV, KDA>(nxt, p, bt + 1, h, hk, row0, col0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     float kf[RPL], qf[RPL];
-    load_bf16_row<RPL>(p.k + (bt * p.Hk + hk) * DK + row0, kf);
-    load_bf16_row<RPL>(p.q + (bt * p.Hk + hk) * DK + row0, qf);
-    const uint2 vw = *reinterpret_cast<const uint2*>(p.v + (bt * p.H + h) * DV + col0);
-    const float beta = p.beta[bt * p.H + h];
+    unpack_bf16<RPL>(cur.k, kf);
+    unpack_bf16<RPL>(cur.q, qf);
+    const float beta = cur.beta;
 
     if constexpr (KDA) {
-      const float4* ap = reinterpret_cast<const float4*>(p.alpha + (bt * p.H + h) * DK + row0);
 #pragma unroll
       for (int i = 0; i < RPL / 4; ++i) {
-        const float4 a = ap[i];
+        const float4 a = cur.alpha_vec[i];
         const float av[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -112,7 +176,7 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
         }
       }
     } else {
-      const float a = p.alpha[bt * p.H + h];
+      const float a = cur.alpha;
 #pragma unroll
       for (int m = 0; m < RPL; ++m) {
         s[m].x *= a;
@@ -147,16 +211,20 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
     kq = reduce_r8(kq);
 
     float4 d;
-    d.x = beta * (bf16_lo(vw.x) - u.x);
-    d.y = beta * (bf16_hi(vw.x) - u.y);
-    d.z = beta * (bf16_lo(vw.y) - u.z);
-    d.w = beta * (bf16_hi(vw.y) - u.w);
+    d.x = beta * (bf16_lo(cur.v.x) - u.x);
+    d.y = beta * (bf16_hi(cur.v.x) - u.y);
+    d.z = beta * (bf16_lo(cur.v.y) - u.z);
+    d.w = beta * (bf16_hi(cur.v.y) - u.w);
 #pragma unroll
     for (int m = 0; m < RPL; ++m) {
       s[m].x = fmaf(kf[m], d.x, s[m].x);
       s[m].y = fmaf(kf[m], d.y, s[m].y);
       s[m].z = fmaf(kf[m], d.z, s[m].z);
       s[m].w = fmaf(kf[m], d.w, s[m].w);
+    }
+    if (!MULTI || t + 1 == p.n_commit) {
+#pragma unroll
+      for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
     }
     if (r8 == 0) {
       float4 o;
@@ -166,10 +234,7 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
       o.w = p.scale * fmaf(kq, d.w, w.w);
       *reinterpret_cast<float4*>(p.out + (bt * p.H + h) * DV + col0) = o;
     }
-    if (t + 1 == p.n_commit) {
-#pragma unroll
-      for (int m = 0; m < RPL; ++m) *reinterpret_cast<float4*>(sout + m * DV) = s[m];
-    }
+    if constexpr (MULTI) cur = nxt;
   }
 }
 
@@ -198,10 +263,15 @@ sa_status launch(const char* name, const void* q, const void* k, const void* v, 
   const dim3 grid(static_cast<unsigned>(rows * H));
   {
     sa::ProfScope prof(KDA ? SA_K_KDA : SA_K_GDN, s);
-    if (dk == 128)
-      delta_step_kernel<128, 128, KDA><<<grid, dim3(256), 0, s>>>(p);
+    const bool single = T == 1 && n_commit == 1;
+    if (dk == 128 && single)
+      delta_step_kernel<128, 128, KDA, false><<<grid, dim3(256), 0, s>>>(p);
+    else if (dk == 128)
+      delta_step_kernel<128, 128, KDA, true><<<grid, dim3(256), 0, s>>>(p);
+    else if (single)
+      delta_step_kernel<64, 64, KDA, false><<<grid, dim3(128), 0, s>>>(p);
     else
-      delta_step_kernel<64, 64, KDA><<<grid, dim3(128), 0, s>>>(p);
+      delta_step_kernel<64, 64, KDA, true><<<grid, dim3(128), 0, s>>>(p);
   }
   return sa::check_launch(name);
 }
