@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
+    ap.add_argument("--no-extras", action="store_true", help="skip batch 256, back-to-back and ragged-length cases")
     ap.add_argument("--no-verify", action="store_true", help="skip the 4-token verify measurements")
     ap.add_argument("--no-placement", action="store_true", help="skip the 48-layer placement stack at batch 128")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -186,6 +187,12 @@ def main():
         verify = verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_pages, lens_fa, lens_swa,
                              rec_scale, attn_scale, stream, alg)
 
+    # ---------------------------------------------------------------- other configurations of the same kernels
+    extras = None
+    if not args.no_extras:
+        extras = extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages, lens_swa, lens_swa_h,
+                             rec_scale, attn_scale, stream, g)
+
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
     if not args.no_cpu_baseline:
@@ -215,6 +222,7 @@ def main():
         "cpu_baseline": cpu,
         "placement48": placement,
         "verify4": verify,
+        "extras": extras,
     }
     print(json.dumps(line))
 
@@ -258,6 +266,51 @@ def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_
         nbytes = alg["attn_split_" + name]
         res[name + "_T4"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
                              "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    return res
+
+
+def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages, lens_swa, lens_swa_h, rec_scale, attn_scale,
+                stream, g, reps=12):
+    """Batch 256 for the recurrent mixers (bandwidth saturation), the recurrent steps launched back to back
+    (no read-only kernel in between to hide their write-back), and full attention at ragged lengths."""
+    res = {}
+    for nb, sets in ((256, 4), (64, 8)):
+        for name, kda, fn, kid in (("gdn", False, sa.gdn_decode_step, sa.SA_K_GDN), ("kda", True, sa.kda_decode_step, sa.SA_K_KDA)):
+            x = {n: dev(a) for n, a in gen.recurrent_inputs(1800 + kda + nb, nb, 1, H, H, DK, DV, kda).items()}
+            states = torch.empty((sets, nb * H, DK, DV), dtype=torch.float32, device="cuda")
+            states.normal_(0.0, 0.02, generator=g)
+            out = torch.empty((nb, 1, H, DV), dtype=torch.float32, device="cuda")
+            sa.sa_prof_enable(True)
+            for i in range(reps):
+                s = states[i % sets]
+                fn(x["q"], x["k"], x["v"], x["alpha"], x["beta"], s, s, out, None, None, 0, nb, 1, H, H, DK, DV, rec_scale, 1,
+                   stream)
+            torch.cuda.synchronize()
+            sa.sa_prof_enable(False)
+            _, _, ms = sa.sa_prof_read(kid, reps)
+            avg = sum(ms[2:]) / (len(ms) - 2)
+            nbytes = 2 * nb * H * DK * DV * 4 + nb * (2 * H * DK * 2 + H * DV * 2 + H * DV * 4 + H * 4) + \
+                nb * H * (DK if kda else 1) * 4
+            res["%s_b%d_back_to_back" % (name, nb)] = {
+                "avg_us": round(avg * 1e3, 2), "tokens_per_s": round(nb / (avg * 1e-3), 1),
+                "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del states
+    q = dev(gen.attention_inputs(1820, B, 1, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"])
+    ws_bytes = sa.attn_decode_workspace_bytes(B, 1, HQ, HKV, D, CTX, 0)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    out = torch.empty((B, 1, HQ, D), dtype=torch.float32, device="cuda")
+    sa.sa_prof_enable(True)
+    for _ in range(reps):
+        sa.attn_decode(q, kpool, vpool, n_pages, table, max_pages, lens_swa, None, 0, out, B, 1, HQ, HKV, D, PAGE, CTX, 0,
+                       attn_scale, ws, ws_bytes, stream)
+    torch.cuda.synchronize()
+    sa.sa_prof_enable(False)
+    _, _, ms = sa.sa_prof_read(sa.SA_K_ATTN_SPLIT, reps)
+    sa.sa_prof_read(sa.SA_K_ATTN_MERGE, reps)
+    avg = sum(ms[2:]) / (len(ms) - 2)
+    nbytes = int(lens_swa_h.astype(np.int64).sum()) * 2 * HKV * D * 2
+    res["fa_ragged_U8192_32768"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1),
+                                    "alg_bytes": nbytes, "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     return res
 
 
