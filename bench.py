@@ -148,7 +148,7 @@ def main():
     _, _, split_ms = sa.sa_prof_read(sa.SA_K_ATTN_SPLIT, cap)
     _, _, merge_ms = sa.sa_prof_read(sa.SA_K_ATTN_MERGE, cap)
     fa_ms, swa_ms = split_ms[0::2], split_ms[1::2]          # launch order within a step: FA, then SWA
-    fa_merge_ms, swa_merge_ms = merge_ms[0::2], merge_ms[1::2]
+    fa_merge_ms = merge_ms          # the windowed launch has one range per (request, KV head): no merge kernel
 
     state_bytes = 2 * B * H * DK * DV * 4
     rec_operands = B * (2 * H * DK * 2 + H * DV * 2 + H * DV * 4 + H * 4)     # q,k,v bf16, out fp32, beta
@@ -171,8 +171,7 @@ def main():
         "kda_decode_step": entry(kda_ms, alg["kda_decode_step"]),
         "attn_split_fa": entry(fa_ms, alg["attn_split_fa"]),
         "attn_split_swa": entry(swa_ms, alg["attn_split_swa"]),
-        "attn_merge_fa": {"avg_us": round(sum(fa_merge_ms) / max(len(fa_merge_ms), 1) * 1e3, 2)},
-        "attn_merge_swa": {"avg_us": round(sum(swa_merge_ms) / max(len(swa_merge_ms), 1) * 1e3, 2)},
+        "attn_merge_fa": {"avg_us": round(sum(fa_merge_ms) / max(len(fa_merge_ms), 1) * 1e3, 2), "launches": len(fa_merge_ms)},
     }
     if copy_entry:
         kernels["copy_1GiB"] = copy_entry

@@ -170,7 +170,8 @@ sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_
  * Measurement helpers (not part of the method).
  */
 enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5, SA_K_COUNT = 6 };
-/* While enabled, every launch of the kernels above is bracketed by HIP events on its stream. */
+/* While enabled, every launch of the kernels above carries HIP start/stop events on its stream that
+ * are stamped with the begin and end of the kernel itself. */
 void sa_prof_enable(int on);
 /* Waits for the recorded events of `kernel`, returns their count and summed duration, and forgets them.
  * If ms_each is not NULL (host array of `capacity` floats) the first `capacity` durations are

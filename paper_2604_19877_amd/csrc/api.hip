@@ -33,20 +33,11 @@ sa_status check_launch(const char* what) {
   return SA_OK;
 }
 
-ProfScope::ProfScope(int kernel_id, hipStream_t s) : kernel(kernel_id), stream(s) {
-  if (!g_prof_on) return;
-  if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) {
-    start = stop = nullptr;
-    return;
-  }
-  (void)hipEventRecord(start, stream);
-}
+bool prof_enabled() { return g_prof_on; }
 
-ProfScope::~ProfScope() {
-  if (!start) return;
-  (void)hipEventRecord(stop, stream);
+void prof_record(int kernel_id, hipEvent_t start, hipEvent_t stop) {
   std::lock_guard<std::mutex> lock(g_prof_mutex);
-  g_prof[kernel].push_back({start, stop});
+  g_prof[kernel_id].push_back({start, stop});
 }
 
 }  // namespace sa
@@ -107,10 +98,7 @@ extern "C" sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, v
   size_t blocks = (n16 + 255) / 256;
   if (blocks > 256 * 16) blocks = 256 * 16;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  {
-    sa::ProfScope prof(SA_K_COPY, s);
-    copy_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(static_cast<const uint4*>(src),
-                                                                          static_cast<uint4*>(dst), n16);
-  }
+  sa::launch(SA_K_COPY, copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, static_cast<const uint4*>(src),
+             static_cast<uint4*>(dst), n16);
   return sa::check_launch("sa_copy_bytes");
 }

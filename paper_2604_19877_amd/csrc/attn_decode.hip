@@ -419,16 +419,10 @@ extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* v
   p.scale_log2 = scale * 1.4426950408889634f;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  {
-    sa::ProfScope prof(SA_K_ATTN_SPLIT, s);
-    attn_split_kernel<<<dim3(Hkv, sp.nsplit, rows), dim3(256), kOccupancyPadBytes, s>>>(p);
-  }
+  sa::launch(SA_K_ATTN_SPLIT, attn_split_kernel, dim3(Hkv, sp.nsplit, rows), dim3(256), kOccupancyPadBytes, s, p);
   sa_status st = sa::check_launch("attn_decode (split kernel)");
   if (st != SA_OK || sp.nsplit == 1) return st;
-  {
-    sa::ProfScope prof(SA_K_ATTN_MERGE, s);
-    attn_merge_kernel<<<dim3(static_cast<unsigned>(rows * Hkv * R)), dim3(128), 0, s>>>(p);
-  }
+  sa::launch(SA_K_ATTN_MERGE, attn_merge_kernel, dim3(static_cast<unsigned>(rows * Hkv * R)), dim3(128), 0, s, p);
   return sa::check_launch("attn_decode (merge kernel)");
 }
 
@@ -449,9 +443,6 @@ extern "C" sa_status kv_append(const void* k_new, const void* v_new, void* kpool
   AppendParams p{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), static_cast<uint16_t*>(kpool),
                  static_cast<uint16_t*>(vpool), page_table, positions, n_pages, max_pages, T, Hkv};
   hipStream_t s = static_cast<hipStream_t>(stream);
-  {
-    sa::ProfScope prof(SA_K_KV_APPEND, s);
-    kv_append_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(128), 0, s>>>(p);
-  }
+  sa::launch(SA_K_KV_APPEND, kv_append_kernel, dim3(static_cast<unsigned>(blocks)), dim3(128), 0, s, p);
   return sa::check_launch(name);
 }

@@ -1,6 +1,7 @@
 // Internal helpers shared by the translation units of libsamixers (host side only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdarg>
 #include <cstdint>
@@ -15,14 +16,25 @@ sa_status fail(sa_status code, const char* fmt, ...);
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-// Event bracketing of one kernel launch when profiling is enabled (see sa_prof_enable).
-struct ProfScope {
-  int kernel;
-  hipStream_t stream;
-  hipEvent_t start = nullptr, stop = nullptr;
-  ProfScope(int kernel_id, hipStream_t s);
-  ~ProfScope();
-};
+// Profiling support (see sa_prof_enable): when enabled, a launch carries a start and a stop event
+// that the runtime stamps with the kernel's own begin and end, so the recorded duration is the
+// kernel's, without the dispatch gaps that events recorded around a launch would include.
+bool prof_enabled();
+void prof_record(int kernel_id, hipEvent_t start, hipEvent_t stop);
+
+template <typename K, typename... Args>
+inline void launch(int kernel_id, K kernel, dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t stream, Args... args) {
+  if (prof_enabled()) {
+    hipEvent_t start = nullptr, stop = nullptr;
+    if (hipEventCreate(&start) == hipSuccess && hipEventCreate(&stop) == hipSuccess) {
+      hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, start, stop, 0, args...);
+      prof_record(kernel_id, start, stop);
+      return;
+    }
+    if (start) (void)hipEventDestroy(start);
+  }
+  hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args...);
+}
 
 // Turns the sticky launch error (if any) into a status.
 sa_status check_launch(const char* what);

@@ -261,18 +261,16 @@ sa_status launch(const char* name, const void* q, const void* k, const void* v, 
                 alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale, n_commit};
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid(static_cast<unsigned>(rows * H));
-  {
-    sa::ProfScope prof(KDA ? SA_K_KDA : SA_K_GDN, s);
-    const bool single = T == 1 && n_commit == 1;
-    if (dk == 128 && single)
-      delta_step_kernel<128, 128, KDA, false><<<grid, dim3(256), 0, s>>>(p);
-    else if (dk == 128)
-      delta_step_kernel<128, 128, KDA, true><<<grid, dim3(256), 0, s>>>(p);
-    else if (single)
-      delta_step_kernel<64, 64, KDA, false><<<grid, dim3(128), 0, s>>>(p);
-    else
-      delta_step_kernel<64, 64, KDA, true><<<grid, dim3(128), 0, s>>>(p);
-  }
+  const int kid = KDA ? SA_K_KDA : SA_K_GDN;
+  const bool single = T == 1 && n_commit == 1;
+  if (dk == 128 && single)
+    sa::launch(kid, delta_step_kernel<128, 128, KDA, false>, grid, dim3(256), 0, s, p);
+  else if (dk == 128)
+    sa::launch(kid, delta_step_kernel<128, 128, KDA, true>, grid, dim3(256), 0, s, p);
+  else if (single)
+    sa::launch(kid, delta_step_kernel<64, 64, KDA, false>, grid, dim3(128), 0, s, p);
+  else
+    sa::launch(kid, delta_step_kernel<64, 64, KDA, true>, grid, dim3(128), 0, s, p);
   return sa::check_launch(name);
 }
 
