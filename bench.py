@@ -294,6 +294,33 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
                 "avg_us": round(avg * 1e3, 2), "tokens_per_s": round(nb / (avg * 1e-3), 1),
                 "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
             del states
+    # whole-block step: convolution + SiLU, L2 norm, gates, state update and gated RMS norm in one launch
+    for name, kda, fn, kid in (("gdn", False, sa.gdn_block_decode, sa.SA_K_GDN_BLOCK), ("kda", True, sa.kda_block_decode, sa.SA_K_KDA_BLOCK)):
+        taps, sets = 4, 8
+        hp = gen.block_inputs(1830 + kda, B, H, H, DK, DV, taps, kda)
+        x = {n: dev(a) for n, a in hp.items()}
+        io = sa.make_block_io(xq=x["xq"], xk=x["xk"], xv=x["xv"], wq=x["wq"], wk=x["wk"], wv=x["wv"], conv_q_in=x["conv_q"],
+                              conv_k_in=x["conv_k"], conv_v_in=x["conv_v"], conv_q_out=x["conv_q"], conv_k_out=x["conv_k"],
+                              conv_v_out=x["conv_v"], conv_taps=taps, beta_raw=x["beta_raw"], alpha_raw=x["alpha_raw"],
+                              A_log=x["A_log"], dt_bias=x["dt_bias"], z=x["z"], norm_weight=x["norm_weight"], norm_eps=1e-5,
+                              gate_act=0)
+        states = torch.empty((sets, B * H, DK, DV), dtype=torch.float32, device="cuda")
+        states.normal_(0.0, 0.02, generator=g)
+        out = torch.empty((B, H, DV), dtype=torch.float32, device="cuda")
+        sa.sa_prof_enable(True)
+        for i in range(reps):
+            s = states[i % sets]
+            fn(io, s, s, out, None, None, 0, B, H, H, DK, DV, rec_scale, stream)
+        torch.cuda.synchronize()
+        sa.sa_prof_enable(False)
+        _, _, ms = sa.sa_prof_read(kid, reps)
+        avg = sum(ms[2:]) / (len(ms) - 2)
+        nbytes = 2 * B * H * DK * DV * 4 + sum(a.nbytes for n, a in hp.items() if n[0] in "xz") + \
+            2 * sum(hp[n].nbytes for n in ("conv_q", "conv_k", "conv_v")) + B * H * DV * 4
+        res["%s_block_b64_back_to_back" % name] = {
+            "avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1), "alg_bytes": nbytes,
+            "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del states
     q = dev(gen.attention_inputs(1820, B, 1, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"])
     ws_bytes = sa.attn_decode_workspace_bytes(B, 1, HQ, HKV, D, CTX, 0)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")

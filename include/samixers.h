@@ -72,6 +72,51 @@ sa_status kda_decode_step(const void* q, const void* k, const void* v, const flo
                           int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Whole-block decode step of a recurrent mixer: the state update above with the block's own pre- and
+ * post-processing fused around it in one launch (Appendix B: a short causal 1-D convolution with SiLU on
+ * Q, K and V, L2-normalised q and k, beta = sigmoid(beta_raw), log-decay
+ * g = -exp(A_log) * softplus(alpha_raw + dt_bias), gated RMS normalisation of the read-out with z; Section 6:
+ * decode "updates the state in-place with incremental convolution updates").  One new token per row.
+ *
+ * Per processed row b (slot s = slot_idx ? slot_idx[b] : b), with C the channel count of a stream
+ * (Hk*dk for q and k, H*dv for v) and Kc = conv_taps:
+ *     y[c]   = SiLU( sum_{j<Kc-1} w[j][c] * conv_in[s][j][c] + w[Kc-1][c] * x[b][c] )
+ *     conv_out[s] = (conv_in[s][1..Kc-2], x[b])                      (the Kc-1 most recent inputs, oldest first)
+ *     q, k   = y / sqrt(sum_head(y^2) + 1e-6) per head;   v = y
+ *     beta   = sigmoid(beta_raw[b,h]);   alpha = exp(-exp(A_log[h]) * softplus(alpha_raw + dt_bias))
+ *              gdn: alpha_raw [B,H], dt_bias [H];   kda: alpha_raw [B,H,dk], dt_bias [H,dk] (one gate per key channel)
+ *     (o, S) = the gdn / kda step above with these q, k, v, alpha, beta
+ *     out[b,h,:] = norm_weight * o / sqrt(mean(o^2) + norm_eps) * act(z[b,h,:]),  act = SiLU (gate_act 0) or sigmoid (1)
+ * The paper names these operations but prints no formula for the two normalisations, for KDA's gate or for the
+ * output gate; the forms above are this library's reading.
+ *
+ *   xq, xk   bf16 [B,Hk,dk]     xv, z  bf16 [B,H,dv]       wq, wk fp32 [Kc][Hk*dk]    wv fp32 [Kc][H*dv]
+ *   conv_*   bf16 [slots][Kc-1][C]; *_out may equal *_in when Hk == H (each channel then has one reader);
+ *            with Hk < H the q and k buffers must be distinct from their inputs
+ *   beta_raw, alpha_raw, A_log, dt_bias, norm_weight fp32;  state and out as for the plain step
+ * Supported: (dk,dv) in {(64,64),(128,128)}, 2 <= conv_taps <= 4.
+ */
+typedef struct {
+  const void *xq, *xk, *xv;
+  const float *wq, *wk, *wv;
+  const void *conv_q_in, *conv_k_in, *conv_v_in;
+  void *conv_q_out, *conv_k_out, *conv_v_out;
+  int conv_taps;
+  const float *beta_raw, *alpha_raw, *A_log, *dt_bias;
+  const void* z;
+  const float* norm_weight;
+  float norm_eps;
+  int gate_act;
+} sa_block_io;
+
+sa_status gdn_block_decode(const sa_block_io* io, const float* state_in, float* state_out, float* out,
+                           const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                           int B, int H, int Hk, int dk, int dv, float scale, void* stream);
+sa_status kda_block_decode(const sa_block_io* io, const float* state_in, float* state_out, float* out,
+                           const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                           int B, int H, int Hk, int dk, int dv, float scale, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Paged KV cache (Section 6, "Heterogeneous state": KV caches grow with the sequence for FA and are
  * bounded at the window for SWA; the paper fixes no in-page order, the one below is this library's).
  *
@@ -169,7 +214,8 @@ sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_
 /* ---------------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method).
  */
-enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5, SA_K_COUNT = 6 };
+enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5,
+       SA_K_GDN_BLOCK = 6, SA_K_KDA_BLOCK = 7, SA_K_COUNT = 8 };
 /* While enabled, every launch of the kernels above carries HIP start/stop events on its stream that
  * are stamped with the begin and end of the kernel itself. */
 void sa_prof_enable(int on);

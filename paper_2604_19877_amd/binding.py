@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsamixers.so")
 
 SA_OK, SA_EINVAL, SA_EUNSUPPORTED, SA_EHIP, SA_EWORKSPACE = 0, -1, -2, -3, -4
-SA_K_GDN, SA_K_KDA, SA_K_ATTN_SPLIT, SA_K_ATTN_MERGE, SA_K_KV_APPEND, SA_K_COPY = range(6)
+SA_K_GDN, SA_K_KDA, SA_K_ATTN_SPLIT, SA_K_ATTN_MERGE, SA_K_KV_APPEND, SA_K_COPY, SA_K_GDN_BLOCK, SA_K_KDA_BLOCK = range(8)
 
 
 class SaError(RuntimeError):
@@ -37,12 +37,23 @@ class sa_layer_io(ctypes.Structure):
                 ("out", c_void_p)]
 
 
+class sa_block_io(ctypes.Structure):
+    _fields_ = [("xq", c_void_p), ("xk", c_void_p), ("xv", c_void_p), ("wq", c_void_p), ("wk", c_void_p), ("wv", c_void_p),
+                ("conv_q_in", c_void_p), ("conv_k_in", c_void_p), ("conv_v_in", c_void_p),
+                ("conv_q_out", c_void_p), ("conv_k_out", c_void_p), ("conv_v_out", c_void_p), ("conv_taps", c_int),
+                ("beta_raw", c_void_p), ("alpha_raw", c_void_p), ("A_log", c_void_p), ("dt_bias", c_void_p),
+                ("z", c_void_p), ("norm_weight", c_void_p), ("norm_eps", c_float), ("gate_act", c_int)]
+
+
+_BLOCK_ARGS = [ctypes.POINTER(sa_block_io)] + [c_void_p] * 5 + [c_int] * 6 + [c_float, c_void_p]
 _RECURRENT_ARGS = [c_void_p] * 10 + [c_int] * 7 + [c_float, c_int, c_void_p]
 _SIGNATURES = {
     "sa_last_error": (c_char_p, []),
     "sa_version": (c_int, []),
     "gdn_decode_step": (c_int, _RECURRENT_ARGS),
     "kda_decode_step": (c_int, _RECURRENT_ARGS),
+    "gdn_block_decode": (c_int, _BLOCK_ARGS),
+    "kda_block_decode": (c_int, _BLOCK_ARGS),
     "kv_append": (c_int, [c_void_p] * 4 + [c_int, c_void_p, c_int, c_void_p] + [c_int] * 5 + [c_void_p]),
     "attn_decode_workspace_bytes": (c_size_t, [c_int] * 7),
     "attn_decode": (c_int, [c_void_p] * 3 + [c_int, c_void_p, c_int, c_void_p, c_void_p, c_int, c_void_p] + [c_int] * 8
@@ -127,6 +138,30 @@ def kda_decode_step(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, re
                     n_commit, stream=None):
     _recurrent(lib().kda_decode_step, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
                Hk, dk, dv, scale, n_commit, stream)
+
+
+def make_block_io(**kw):
+    """Fills an sa_block_io from tensors / numbers given by field name."""
+    io = sa_block_io()
+    for name, _ in sa_block_io._fields_:
+        val = kw.get(name)
+        if name in ("conv_taps", "gate_act"):
+            setattr(io, name, int(val or 0))
+        elif name == "norm_eps":
+            io.norm_eps = float(val or 0.0)
+        else:
+            setattr(io, name, _ptr(val))
+    return io
+
+
+def gdn_block_decode(io, state_in, state_out, out, slot_idx, req_idx, n_req, B, H, Hk, dk, dv, scale, stream=None):
+    _check(lib().gdn_block_decode(ctypes.byref(io), _ptr(state_in), _ptr(state_out), _ptr(out), _ptr(slot_idx), _ptr(req_idx),
+                                  n_req, B, H, Hk, dk, dv, scale, _stream(stream)))
+
+
+def kda_block_decode(io, state_in, state_out, out, slot_idx, req_idx, n_req, B, H, Hk, dk, dv, scale, stream=None):
+    _check(lib().kda_block_decode(ctypes.byref(io), _ptr(state_in), _ptr(state_out), _ptr(out), _ptr(slot_idx), _ptr(req_idx),
+                                  n_req, B, H, Hk, dk, dv, scale, _stream(stream)))
 
 
 def kv_append(k_new, v_new, kpool, vpool, n_pages, page_table, max_pages, positions, B, T, Hkv, D, page_size, stream=None):

@@ -14,6 +14,7 @@
 // r8*dk/8 .. (r8+1)*dk/8-1, i.e. dk/8 float4 registers.  One load instruction of the wavefront
 // fetches 8 full 128-byte lines.  The key-dimension sums finish with a 3-step butterfly over r8.
 #include "common.h"
+#include "delta_device.h"
 
 namespace {
 
@@ -32,41 +33,6 @@ struct DeltaParams {
   float scale;
   int n_commit;
 };
-
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-// The state is touched exactly once per step, so it is loaded and stored with the non-temporal
-// hint: measured back to back over 1 GiB of states on MI355X this is ~14 % faster than plain
-// accesses, and a whole decode step (GDN, KDA, FA, SWA in turn) ~1 % faster.  Plain accesses only
-// win when the same 128 MiB of state is stepped again while it still sits in the 256 MB last-level
-// cache, which a model with dozens of recurrent layers never does.
-__device__ __forceinline__ float4 load_state(const float* p) {
-  const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  return float4{t[0], t[1], t[2], t[3]};
-}
-__device__ __forceinline__ void store_state(float* p, const float4& v) {
-  const f32x4 t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
-}
-
-// A per-(row, head) scalar read through the constant address space: the index is the same for the
-// whole workgroup, so this becomes a scalar-cache load instead of 64 identical vector loads.  The
-// gates are inputs and are not written while the kernel runs.
-typedef const __attribute__((address_space(4))) float* const_f32_ptr;
-__device__ __forceinline__ float load_uniform(const float* p, size_t i) {
-  return reinterpret_cast<const_f32_ptr>(reinterpret_cast<uintptr_t>(p))[i];
-}
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// Sum over the 8 lanes that share c8 (lane bits 3..5).
-__device__ __forceinline__ float reduce_r8(float x) {
-  x += __shfl_xor(x, 8);
-  x += __shfl_xor(x, 16);
-  x += __shfl_xor(x, 32);
-  return x;
-}
 
 // Operands of one step as they arrive from memory (bf16 still packed).
 template <int RPL, bool KDA>

@@ -76,6 +76,28 @@ def recurrent_state(seed: int, n_tiles: int, dk: int, dv: int, std: float = 0.02
     return (rng.standard_normal((n_tiles, dk, dv), dtype=np.float32) * np.float32(std)).astype(np.float32)
 
 
+def block_inputs(seed: int, B: int, H: int, Hk: int, dk: int, dv: int, taps: int, per_channel_gate: bool, n_slots=None):
+    """Operands of one decode token of a whole GDN / KDA block (before the convolution): projection
+    outputs xq, xk [B,Hk,dk], xv and z [B,H,dv] ~ N(0,1) bf16; convolution histories (the taps-1
+    previous inputs, oldest first) [n_slots,taps-1,C] ~ N(0,1) bf16; depthwise taps fp32 [taps,C] ~
+    N(0, 1/taps); raw gates ~ N(0,1); A_log ~ log 0.1 + N(0, 0.3^2) per head; dt_bias ~ N(0,1) per head
+    (GDN) or per (head, channel) (KDA); norm weight 1 + 0.1 N(0,1)."""
+    rng = np.random.default_rng(seed)
+    n_slots = B if n_slots is None else n_slots
+    Cqk, Cv = Hk * dk, H * dv
+    nb = lambda shape: _normal_bf16(rng, shape)
+    f32 = lambda shape, scale=1.0: (rng.standard_normal(shape) * scale).astype(np.float32)
+    return {
+        "xq": nb((B, Hk, dk)), "xk": nb((B, Hk, dk)), "xv": nb((B, H, dv)), "z": nb((B, H, dv)),
+        "conv_q": nb((n_slots, taps - 1, Cqk)), "conv_k": nb((n_slots, taps - 1, Cqk)), "conv_v": nb((n_slots, taps - 1, Cv)),
+        "wq": f32((taps, Cqk), taps ** -0.5), "wk": f32((taps, Cqk), taps ** -0.5), "wv": f32((taps, Cv), taps ** -0.5),
+        "beta_raw": f32((B, H)), "alpha_raw": f32((B, H, dk) if per_channel_gate else (B, H)),
+        "A_log": (np.log(0.1) + rng.standard_normal(H) * 0.3).astype(np.float32),
+        "dt_bias": f32((H, dk) if per_channel_gate else (H,)),
+        "norm_weight": (1.0 + 0.1 * rng.standard_normal(dv)).astype(np.float32),
+    }
+
+
 # ----------------------------------------------------------------------------- paged attention
 def context_lengths(seed: int, B: int, lo: int, hi: int) -> np.ndarray:
     """Context lengths uniform in [lo, hi], int32 (not page aligned)."""
