@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--no-extras", action="store_true", help="skip batch 256, back-to-back and ragged-length cases")
     ap.add_argument("--no-verify", action="store_true", help="skip the 4-token verify measurements")
     ap.add_argument("--no-placement", action="store_true", help="skip the 48-layer placement stack at batch 128")
+    ap.add_argument("--cost-table", action="store_true",
+                    help="only fit the per-mixer cost model 1/throughput = sum_m c_m n_m over 14 allocations of a 48-layer "
+                         "stack (batch 32, 16384-token contexts) and print it")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the plain 1 GiB copy kernel 3 times after the timed region (counter calibration)")
     return ap.parse_args()
@@ -63,6 +66,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+    if args.cost_table:
+        print(json.dumps(cost_table(np, torch, gen, stream)))
+        return
 
     def dev(a):
         a = np.ascontiguousarray(a)
@@ -338,6 +344,45 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
     res["fa_ragged_U8192_32768"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1),
                                     "alg_bytes": nbytes, "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     return res
+
+
+def cost_table(np, torch, gen, stream, batch=32, ctx=16384, steps=6):
+    """The paper's linear cost model (Section 4, "Cost model": 1/throughput = sum over mixers of c_m * n_m,
+    fitted on measured placements) for the mixers-only stack on this GPU: all requests of a batch share one
+    placement, as in the paper's single-preset measurements."""
+    from paper_2604_19877_amd.workloads import PlacementWorkload
+    allocations = [(48, 0, 0, 0), (0, 48, 0, 0), (0, 0, 48, 0), (0, 0, 0, 48), (24, 24, 0, 0), (24, 0, 24, 0), (24, 0, 0, 24),
+                   (12, 12, 12, 12), (0, 16, 16, 16), (6, 30, 6, 6), (3, 25, 4, 16), (0, 10, 5, 33), (12, 26, 6, 4), (0, 30, 5, 13)]
+    rows, times = [], []
+    for i, (f, s_, k, g_) in enumerate(allocations):
+        placement = gen.placement_string(6000 + i, 48, {"F": f, "S": s_, "K": k, "G": g_})
+        w = PlacementWorkload(B=batch, L=48, ctx=ctx, window=WINDOW, T=1, seed=6100 + i, placements=[placement])
+        try:
+            for _ in range(2):
+                w.step(stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                w.step(stream)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+        finally:
+            w.close()
+        del w
+        torch.cuda.empty_cache()
+        rows.append((f, s_, k, g_))
+        times.append(ms * 1e-3 / batch)                      # seconds per token = 1 / throughput
+    A, y = np.array(rows, dtype=np.float64), np.array(times)
+    c, *_ = np.linalg.lstsq(A, y, rcond=None)
+    pred = A @ c
+    r2 = 1.0 - float(np.sum((y - pred) ** 2) / np.sum((y - y.mean()) ** 2))
+    return {"workload": "48-layer mixers-only stack, batch %d, contexts %d, one placement per run, w=%d" % (batch, ctx, WINDOW),
+            "allocations_F_S_K_G": rows, "ms_per_step": [round(t * batch * 1e3, 3) for t in times],
+            "cost_us_per_layer_per_token": dict(zip("FSKG", [round(float(x) * 1e6, 4) for x in c])),
+            "relative_cost": dict(zip(["FA", "SWA", "KDA", "GDN"], [round(float(x / c[0]), 4) for x in c])),
+            "r2": round(r2, 5), "mean_abs_rel_err": round(float(np.mean(np.abs(pred - y) / y)), 4),
+            "paper_relative_cost_context_only": {"FA": 1.0, "SWA": 0.48, "KDA": 0.21, "GDN": 0.14,
+                                                 "note": "1xH100, whole 15B model incl. FFNs, vLLM, 16k, regression over 84 placements"}}
 
 
 def placement_stack(torch, sa, stream, steps=8, warmup=2):

@@ -38,10 +38,12 @@ class PlacementWorkload:
     state only for the requests that run a recurrent mixer there (slot maps).
     """
 
-    def __init__(self, B=128, L=48, ctx=16384, window=4096, T=1, seed=5000, n_placements=3):
+    def __init__(self, B=128, L=48, ctx=16384, window=4096, T=1, seed=5000, n_placements=3, placements=None):
         import torch
         self.B, self.L, self.ctx, self.window, self.T = B, L, ctx, window, T
-        self.placements = [gen.placement_string(seed + 1 + i, L) for i in range(n_placements)]
+        if placements is None:
+            placements = [gen.placement_string(seed + 1 + i, L) for i in range(n_placements)]
+        self.placements, n_placements = list(placements), len(placements)
         self.pid = (np.arange(B) % n_placements).astype(np.int32)
         self.max_pages = (ctx + PAGE - 1) // PAGE
         first_win = max(0, ctx - T + 1 - window) // PAGE
@@ -80,7 +82,8 @@ class PlacementWorkload:
             ops = gen.recurrent_inputs(seed + 100 + 2 * l, B, T, H, H, DK, DV, False)
             ops_vec = gen.recurrent_inputs(seed + 101 + 2 * l, B, T, H, H, DK, DV, True)
             state = torch.empty((max(len(rec_rows), 1) * H, DK, DV), dtype=torch.float32, device="cuda")
-            state.normal_(0.0, 0.02, generator=g)
+            if len(rec_rows):
+                state.normal_(0.0, 0.02, generator=g)
             t = {"q": dev(ops["q"]), "k": dev(ops["k"]), "v": dev(ops["v"]), "alpha_scalar": dev(ops["alpha"]),
                  "alpha_vec": dev(ops_vec["alpha"]), "beta": dev(ops["beta"]), "state": state, "slot_idx": dev(slot),
                  "page_table": dev(table), "out": torch.zeros((B, T, H, DV), dtype=torch.float32, device="cuda")}
