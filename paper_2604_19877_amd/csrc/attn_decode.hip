@@ -75,28 +75,59 @@ SplitPlan plan_splits(int n_req, int Hkv, int T, int max_seq_len, int window) {
     if (span < max_pages) max_pages = span;
   }
   if (max_pages < 1) max_pages = 1;
-  // Workgroups wanted over the whole launch.  Measured on MI355X: the K/V stream runs fastest with
-  // 2 workgroups (8 wavefronts) per CU and long page ranges; more, shorter ranges only pay when
-  // sequence lengths are ragged (full attention), where they even out the load.  A window bounds
-  // every sequence's work equally, so one or two ranges per (request, KV head) are enough.
-  // SAMIXERS_ATTN_TARGET_GROUPS overrides the choice for tuning runs; it is read once.
+  const long long pairs = static_cast<long long>(n_req) * Hkv;
+  auto make = [&](long long ranges) {
+    long long per = (max_pages + ranges - 1) / ranges;
+    per = (per + kWaves - 1) / kWaves * kWaves;
+    SplitPlan sp;
+    sp.pages_per_split = static_cast<int>(per);
+    sp.nsplit = static_cast<int>((max_pages + per - 1) / per);
+    return sp;
+  };
+  // SAMIXERS_ATTN_TARGET_GROUPS=<workgroups wanted per launch> bypasses the model below in tuning runs.
   static const long long forced = [] {
     const char* e = std::getenv("SAMIXERS_ATTN_TARGET_GROUPS");
     long long v = e ? std::atoll(e) : 0;
     return v > 0 ? v : 0LL;
   }();
-  const long long target_groups = forced ? forced : (window > 0 ? 512 : 2048);
-  long long pairs = static_cast<long long>(n_req) * Hkv;
-  long long want = (target_groups + pairs - 1) / pairs;
-  long long most = (max_pages + 7) / 8;  // at least 8 pages (2 per wavefront) per range
-  if (want > most) want = most;
-  if (want < 1) want = 1;
-  long long per = (max_pages + want - 1) / want;
-  per = (per + kWaves - 1) / kWaves * kWaves;
-  SplitPlan sp;
-  sp.pages_per_split = static_cast<int>(per);
-  sp.nsplit = static_cast<int>((max_pages + per - 1) / per);
-  return sp;
+  if (forced) {
+    long long want = (forced + pairs - 1) / pairs;
+    const long long most = (max_pages + 7) / 8;
+    want = want > most ? most : want;
+    return make(want < 1 ? 1 : want);
+  }
+  // Cost model.  The K/V stream runs fastest with 2 workgroups per CU (see kOccupancyPadBytes), so a
+  // launch of N equal workgroups takes about ceil(N / slots) rounds, slots = 2 * CUs; a workgroup costs
+  // its pages plus a start-up (lengths, page ids, first page: three dependent memory latencies, about
+  // 8 pages' worth of streaming time).  Pick the range count that minimises rounds * (pages + start-up).
+  // Full attention keeps at least 4 ranges when the context allows: real lengths are ragged and only
+  // known on the device, and finer ranges even out the load (measured: 978 us against 1060 us for one
+  // range at lengths uniform in [8192, 32768]).
+  static const long long slots = [] {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess || prop.multiProcessorCount < 1) {
+      (void)hipGetLastError();
+      return 512LL;
+    }
+    return 2LL * prop.multiProcessorCount;
+  }();
+  const long long startup_pages = 8, min_pages = 16;
+  long long most = max_pages / min_pages;
+  most = most < 1 ? 1 : (most > 64 ? 64 : most);
+  long long least = window > 0 ? 1 : 4;
+  least = least > most ? most : least;
+  long long best = least, best_cost = -1;
+  for (long long n = least; n <= most; ++n) {
+    const SplitPlan sp = make(n);
+    const long long groups = pairs * sp.nsplit;
+    const long long cost = ((groups + slots - 1) / slots) * (sp.pages_per_split + startup_pages);
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best = n;
+    }
+  }
+  return make(best);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
