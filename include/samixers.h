@@ -31,7 +31,8 @@ enum {
   SA_EINVAL = -1,       /* null/misaligned pointer, inconsistent shape, bad placement string */
   SA_EUNSUPPORTED = -2, /* a size outside what the kernels are built for                      */
   SA_EHIP = -3,         /* a HIP call or launch failed                                        */
-  SA_EWORKSPACE = -4    /* workspace too small                                                */
+  SA_EWORKSPACE = -4,   /* workspace too small                                                */
+  SA_ENOMEM = -5        /* the page pool has too few free pages                               */
 };
 
 /* Message of the last failure on this thread; static storage, never freed by the caller. */
@@ -210,6 +211,44 @@ size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, i
  * layer over that mixer's request list.  Recurrent layers commit all T steps in place. */
 sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,
                            float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Unified page pool (Section 6, "Heterogeneous state": FA caches grow with the sequence, SWA caches are
+ * bounded at the window, GDN / KDA keep a fixed-size state, and a unified page size lets one paged memory
+ * manager serve all layer kinds).  Host-side bookkeeping only: the caller allocates one device arena of
+ * n_pages * sa_pool_page_bytes() bytes and the pool hands out page numbers.
+ *
+ * One unified page is the recurrent state of one (sequence, layer): H*dk*dv*4 bytes.  For an attention
+ * layer the same page holds the K and V blocks of sa_pool_tokens_per_page() tokens: first the K blocks of
+ * its 16-token pages, then, from the middle of the page, their V blocks.  With
+ *     kpool = arena,  vpool = arena + page_bytes/2,  n_pages(kernel) = n_pages * sa_pool_kv_id_stride()
+ * the 16-token page i of unified page u has the kernel page id u * sa_pool_kv_id_stride() + i, and the
+ * attention and append entry points above work on the arena unchanged.  For a recurrent layer
+ *     state = (float*)arena,  slot = u
+ * (convolution histories, if used, live in caller arrays indexed by the same slot).
+ * Requires page_bytes to be a multiple of 2 * Hkv*16*D*2 (SA_EUNSUPPORTED otherwise).
+ *
+ * A sequence names a placement (one of F,S,K,G per layer).  sa_pool_seq_create gives every K/G layer its
+ * state page; sa_pool_seq_reserve(len) makes tokens [0,len) addressable on F layers and the last
+ * `window` + `slack` tokens on S layers, returning pages that fell out of the window to the pool; it
+ * either succeeds completely or changes nothing (SA_ENOMEM).  Not thread-safe.
+ */
+typedef struct sa_pool sa_pool;
+sa_status sa_pool_create(int n_pages, const sa_shapes* shapes, int n_layers, sa_pool** pool_out);
+void sa_pool_destroy(sa_pool* pool);
+size_t sa_pool_page_bytes(const sa_pool* pool);
+int sa_pool_tokens_per_page(const sa_pool* pool);
+int sa_pool_kv_id_stride(const sa_pool* pool);
+int sa_pool_free_pages(const sa_pool* pool);
+sa_status sa_pool_seq_create(sa_pool* pool, const char* placement, int* seq_id_out);
+sa_status sa_pool_seq_reserve(sa_pool* pool, int seq_id, int len, int window, int slack);
+sa_status sa_pool_seq_free(sa_pool* pool, int seq_id);
+int sa_pool_seq_pages(const sa_pool* pool, int seq_id);      /* pages the sequence holds now; -1 if unknown */
+/* Host tables of one layer for a batch of sequences: page_table [B,max_pages] in kernel page ids (-1 where
+ * nothing is mapped or the layer is not an attention layer for that sequence), slot [B] = state page of a
+ * recurrent layer (-1 otherwise).  Either output may be NULL. */
+sa_status sa_pool_layer_tables(const sa_pool* pool, const int32_t* seq_ids, int B, int layer, int32_t* page_table,
+                               int max_pages, int32_t* slot);
 
 /* ---------------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method).

@@ -13,7 +13,7 @@ from ctypes import c_char, c_char_p, c_float, c_int, c_int32, c_size_t, c_void_p
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsamixers.so")
 
-SA_OK, SA_EINVAL, SA_EUNSUPPORTED, SA_EHIP, SA_EWORKSPACE = 0, -1, -2, -3, -4
+SA_OK, SA_EINVAL, SA_EUNSUPPORTED, SA_EHIP, SA_EWORKSPACE, SA_ENOMEM = 0, -1, -2, -3, -4, -5
 SA_K_GDN, SA_K_KDA, SA_K_ATTN_SPLIT, SA_K_ATTN_MERGE, SA_K_KV_APPEND, SA_K_COPY, SA_K_GDN_BLOCK, SA_K_KDA_BLOCK = range(8)
 
 
@@ -65,6 +65,17 @@ _SIGNATURES = {
     "placement_workspace_bytes": (c_size_t, [c_void_p, ctypes.POINTER(sa_shapes), c_int, c_int, c_int]),
     "placement_decode": (c_int, [c_void_p, ctypes.POINTER(sa_layer_io), ctypes.POINTER(sa_shapes), c_int, c_int, c_float,
                                  c_float, c_void_p, c_size_t, c_void_p]),
+    "sa_pool_create": (c_int, [c_int, ctypes.POINTER(sa_shapes), c_int, ctypes.POINTER(c_void_p)]),
+    "sa_pool_destroy": (None, [c_void_p]),
+    "sa_pool_page_bytes": (c_size_t, [c_void_p]),
+    "sa_pool_tokens_per_page": (c_int, [c_void_p]),
+    "sa_pool_kv_id_stride": (c_int, [c_void_p]),
+    "sa_pool_free_pages": (c_int, [c_void_p]),
+    "sa_pool_seq_create": (c_int, [c_void_p, c_char_p, ctypes.POINTER(c_int)]),
+    "sa_pool_seq_reserve": (c_int, [c_void_p, c_int, c_int, c_int, c_int]),
+    "sa_pool_seq_free": (c_int, [c_void_p, c_int]),
+    "sa_pool_seq_pages": (c_int, [c_void_p, c_int]),
+    "sa_pool_layer_tables": (c_int, [c_void_p, ctypes.POINTER(c_int32), c_int, c_int, c_void_p, c_int, c_void_p]),
     "sa_prof_enable": (None, [c_int]),
     "sa_prof_read": (c_int, [c_int, ctypes.POINTER(c_int), ctypes.POINTER(c_float), ctypes.POINTER(c_float), c_int]),
     "sa_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
@@ -221,6 +232,61 @@ def placement_decode(plan, io, shapes, T, window, attn_scale, rec_scale, workspa
         io = (sa_layer_io * len(io))(*io)
     _check(lib().placement_decode(plan, io, ctypes.byref(shapes), T, window, attn_scale, rec_scale, _ptr(workspace),
                                   workspace_bytes, _stream(stream)))
+
+
+def sa_pool_create(n_pages, shapes, n_layers):
+    pool = c_void_p()
+    _check(lib().sa_pool_create(n_pages, ctypes.byref(shapes), n_layers, ctypes.byref(pool)))
+    return pool
+
+
+def sa_pool_destroy(pool):
+    lib().sa_pool_destroy(pool)
+
+
+def sa_pool_page_bytes(pool) -> int:
+    return lib().sa_pool_page_bytes(pool)
+
+
+def sa_pool_tokens_per_page(pool) -> int:
+    return lib().sa_pool_tokens_per_page(pool)
+
+
+def sa_pool_kv_id_stride(pool) -> int:
+    return lib().sa_pool_kv_id_stride(pool)
+
+
+def sa_pool_free_pages(pool) -> int:
+    return lib().sa_pool_free_pages(pool)
+
+
+def sa_pool_seq_create(pool, placement) -> int:
+    seq = c_int(-1)
+    _check(lib().sa_pool_seq_create(pool, placement.encode(), ctypes.byref(seq)))
+    return seq.value
+
+
+def sa_pool_seq_reserve(pool, seq_id, length, window, slack=0):
+    _check(lib().sa_pool_seq_reserve(pool, seq_id, length, window, slack))
+
+
+def sa_pool_seq_free(pool, seq_id):
+    _check(lib().sa_pool_seq_free(pool, seq_id))
+
+
+def sa_pool_seq_pages(pool, seq_id) -> int:
+    return lib().sa_pool_seq_pages(pool, seq_id)
+
+
+def sa_pool_layer_tables(pool, seq_ids, layer, max_pages):
+    """Returns (page_table int32 [B,max_pages], slot int32 [B]) as numpy arrays (host)."""
+    import numpy as np
+    B = len(seq_ids)
+    ids = (c_int32 * max(B, 1))(*[int(x) for x in seq_ids])
+    table = np.empty((B, max_pages), dtype=np.int32)
+    slot = np.empty(B, dtype=np.int32)
+    _check(lib().sa_pool_layer_tables(pool, ids, B, layer, table.ctypes.data, max_pages, slot.ctypes.data))
+    return table, slot
 
 
 def sa_prof_enable(on):
