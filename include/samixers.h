@@ -155,7 +155,7 @@ sa_status kv_append(const void* k_new, const void* v_new, void* kpool, void* vpo
  *   workspace  at least attn_decode_workspace_bytes(...) bytes, 16-byte aligned; holds the per-split
  *              partial results (running maximum, normaliser, unnormalised output) that a second
  *              kernel merges in a fixed order, so results are run-to-run deterministic.
- * Supported: D = 128, page_size = 16, T * (Hq/Hkv) <= 16.
+ * Supported: D = 128, page_size = 16, T * (Hq/Hkv) <= 32 (e.g. 8 new tokens at 4 query heads per KV head).
  */
 size_t attn_decode_workspace_bytes(int n_req, int T, int Hq, int Hkv, int D, int max_seq_len, int window);
 sa_status attn_decode(const void* q, const void* kpool, const void* vpool, int n_pages,

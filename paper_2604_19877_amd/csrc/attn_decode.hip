@@ -161,6 +161,9 @@ __device__ __forceinline__ void load_page(PageFrags& f, const uint16_t* kpool, c
   }
 }
 
+// NT = number of 16-row query tiles per KV head (1: up to 16 rows, 2: up to 32, e.g. 8 new tokens x 4 heads).
+// K and V fragments are loaded once per page and used for every tile.
+template <int NT>
 __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
   __shared__ float sm_o[kWaves][16][kD];
   __shared__ float sm_m[kWaves][16];
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
   const int b = p.req_idx ? p.req_idx[r] : r;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int row = lane & 15, grp = lane >> 4;
+  const int row16 = lane & 15, grp = lane >> 4;
 
   int L = p.seq_lens[b];
   L = L < p.max_seq_len ? L : p.max_seq_len;
@@ -183,28 +186,36 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
   const int ps = page_first + split * p.pages_per_split;
   const int pe = min(page_end, ps + p.pages_per_split);
 
-  // This lane's query row: new token t_row, head g*G + row%G.  Rows >= R are padding (q = 0).
-  const bool real_row = row < p.R;
-  const int t_row = real_row ? row / p.G : p.T - 1;
-  const int hi_row = L - p.T + t_row + 1;
-  const int lo_row = p.window > 0 ? max(0, hi_row - p.window) : 0;
-
-  bf16x8 qf[4];
-  {
-    uint4 zero = {0u, 0u, 0u, 0u};
+  // This lane's query row in tile n: new token t_row, head g*G + row%G.  Rows >= R are padding (q = 0).
+  bool real_row[NT];
+  int hi_row[NT], lo_row[NT];
+  bf16x8 qf[NT][4];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    const int row = n * 16 + row16;
+    real_row[n] = row < p.R;
+    const int t_row = real_row[n] ? row / p.G : p.T - 1;
+    hi_row[n] = L - p.T + t_row + 1;
+    lo_row[n] = p.window > 0 ? max(0, hi_row[n] - p.window) : 0;
+    const uint4 zero = {0u, 0u, 0u, 0u};
     const uint16_t* qp =
-        p.q + ((static_cast<size_t>(b) * p.T + t_row) * p.Hq + g * p.G + (real_row ? row % p.G : 0)) * kD + grp * 8;
+        p.q + ((static_cast<size_t>(b) * p.T + t_row) * p.Hq + g * p.G + (real_row[n] ? row % p.G : 0)) * kD + grp * 8;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      uint4 w = real_row ? *reinterpret_cast<const uint4*>(qp + i * 32) : zero;
-      qf[i] = __builtin_bit_cast(bf16x8, w);
+      const uint4 w = real_row[n] ? *reinterpret_cast<const uint4*>(qp + i * 32) : zero;
+      qf[n][i] = __builtin_bit_cast(bf16x8, w);
     }
   }
 
-  float m_run = kNegBig, l_run = 0.f;
-  f32x4 o[8];
+  float m_run[NT], l_run[NT];
+  f32x4 o[NT][8];
 #pragma unroll
-  for (int nb = 0; nb < 8; ++nb) o[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int n = 0; n < NT; ++n) {
+    m_run[n] = kNegBig;
+    l_run[n] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) o[n][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
   const int32_t* table = p.page_table + static_cast<size_t>(b) * p.max_pages;
   const int first = ps + wave;
@@ -228,11 +239,6 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
         load_page(nxt, p.kpool, p.vpool, __builtin_amdgcn_readlane(tbl, (it + 1) & 63), p.Hkv, g, lane);
       }
 
-      f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[i]), qf[i], s, 0, 0, 0);
-
       const int j0 = pg * kPage + grp * 4;
       // Slots of a boundary page that hold no live token may contain anything (NaN included), and
       // 0 * NaN would poison the output: clear their V entries.  K needs no such care because a
@@ -250,87 +256,104 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnParams p) {
           cur.v[nb].y &= keep[1];
         }
       }
-      bool ok[4];
-      float sv[4];
-      float m_loc = kNegBig;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        ok[e] = (j0 + e >= lo_row) && (j0 + e < hi_row);
-        sv[e] = ok[e] ? s[e] * p.scale_log2 : kNegBig;
-        m_loc = fmaxf(m_loc, sv[e]);
-      }
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16));
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
-      const float m_new = fmaxf(m_run, m_loc);
-      const float corr = exp2f(m_run - m_new);
-      m_run = m_new;
-      float pv[4];
-      float psum = 0.f;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        pv[e] = ok[e] ? exp2f(sv[e] - m_new) : 0.f;
-        psum += pv[e];
-      }
-      l_run = fmaf(l_run, corr, psum);
-
-      uint2 hi, lo;
-      hi.x = pack_bf16_rne(pv[0], pv[1]);
-      hi.y = pack_bf16_rne(pv[2], pv[3]);
-      lo.x = pack_bf16_rne(pv[0] - __uint_as_float(hi.x << 16), pv[1] - __uint_as_float(hi.x & 0xffff0000u));
-      lo.y = pack_bf16_rne(pv[2] - __uint_as_float(hi.y << 16), pv[3] - __uint_as_float(hi.y & 0xffff0000u));
-      const s16x4 p_hi = __builtin_bit_cast(s16x4, hi);
-      const s16x4 p_lo = __builtin_bit_cast(s16x4, lo);
 
 #pragma unroll
-      for (int nb = 0; nb < 8; ++nb) {
-        f32x4 acc = o[nb];
-        acc[0] *= corr;
-        acc[1] *= corr;
-        acc[2] *= corr;
-        acc[3] *= corr;
-        const s16x4 vf = __builtin_bit_cast(s16x4, cur.v[nb]);
-        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, p_hi, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, p_lo, acc, 0, 0, 0);
-        o[nb] = acc;
+      for (int n = 0; n < NT; ++n) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[i]), qf[n][i], s, 0, 0, 0);
+
+        bool ok[4];
+        float sv[4];
+        float m_loc = kNegBig;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          ok[e] = (j0 + e >= lo_row[n]) && (j0 + e < hi_row[n]);
+          sv[e] = ok[e] ? s[e] * p.scale_log2 : kNegBig;
+          m_loc = fmaxf(m_loc, sv[e]);
+        }
+        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16));
+        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+        const float m_new = fmaxf(m_run[n], m_loc);
+        const float corr = exp2f(m_run[n] - m_new);
+        m_run[n] = m_new;
+        float pv[4];
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          pv[e] = ok[e] ? exp2f(sv[e] - m_new) : 0.f;
+          psum += pv[e];
+        }
+        l_run[n] = fmaf(l_run[n], corr, psum);
+
+        uint2 hi, lo;
+        hi.x = pack_bf16_rne(pv[0], pv[1]);
+        hi.y = pack_bf16_rne(pv[2], pv[3]);
+        lo.x = pack_bf16_rne(pv[0] - __uint_as_float(hi.x << 16), pv[1] - __uint_as_float(hi.x & 0xffff0000u));
+        lo.y = pack_bf16_rne(pv[2] - __uint_as_float(hi.y << 16), pv[3] - __uint_as_float(hi.y & 0xffff0000u));
+        const s16x4 p_hi = __builtin_bit_cast(s16x4, hi);
+        const s16x4 p_lo = __builtin_bit_cast(s16x4, lo);
+
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+          f32x4 acc = o[n][nb];
+          acc[0] *= corr;
+          acc[1] *= corr;
+          acc[2] *= corr;
+          acc[3] *= corr;
+          const s16x4 vf = __builtin_bit_cast(s16x4, cur.v[nb]);
+          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, p_hi, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, p_lo, acc, 0, 0, 0);
+          o[n][nb] = acc;
+        }
       }
       cur = nxt;
     }
   }
 
-  // Merge the 4 wavefronts.  l_run is a per-lane partial over this lane's token group.
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  if (real_row) {
-    if (grp == 0) {
-      sm_m[wave][row] = m_run;
-      sm_l[wave][row] = l_run;
-    }
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb)
-      *reinterpret_cast<float4*>(&sm_o[wave][row][nb * 16 + grp * 4]) = float4{o[nb][0], o[nb][1], o[nb][2], o[nb][3]};
-  }
-  __syncthreads();
-
+  // Merge the 4 wavefronts, one query tile at a time through the same LDS buffer.
   const size_t part = ((static_cast<size_t>(r) * p.Hkv + g) * p.nsplit + split) * p.R;
-  for (int idx = threadIdx.x; idx < p.R * kD; idx += 256) {
-    const int rr = idx / kD, d = idx - rr * kD;
-    float m = sm_m[0][rr];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, sm_m[w][rr]);
-    float l = 0.f, acc = 0.f;
+  for (int n = 0; n < NT; ++n) {
+    float l = l_run[n];                     // per-lane partial over this lane's token group
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (n > 0) __syncthreads();             // the previous tile has been read out
+    if (real_row[n]) {
+      if (grp == 0) {
+        sm_m[wave][row16] = m_run[n];
+        sm_l[wave][row16] = l;
+      }
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float f = exp2f(sm_m[w][rr] - m);
-      l = fmaf(sm_l[w][rr], f, l);
-      acc = fmaf(sm_o[w][rr][d], f, acc);
+      for (int nb = 0; nb < 8; ++nb)
+        *reinterpret_cast<float4*>(&sm_o[wave][row16][nb * 16 + grp * 4]) =
+            float4{o[n][nb][0], o[n][nb][1], o[n][nb][2], o[n][nb][3]};
     }
-    if (p.nsplit == 1) {
-      // The only range of this (request, KV head): finish here, no partials, no merge kernel.
-      const int t = rr / p.G, hq = g * p.G + rr % p.G;
-      p.out[((static_cast<size_t>(b) * p.T + t) * p.Hq + hq) * kD + d] = l > 0.f ? acc / l : 0.f;
-    } else {
-      p.part_o[(part + rr) * kD + d] = acc;
-      if (d == 0) p.part_ml[part + rr] = float2{m, l};
+    __syncthreads();
+
+    const int rows_here = min(16, p.R - n * 16);
+    for (int idx = threadIdx.x; idx < rows_here * kD; idx += 256) {
+      const int r16 = idx / kD, d = idx - r16 * kD;
+      const int rr = n * 16 + r16;
+      float m = sm_m[0][r16];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) m = fmaxf(m, sm_m[w][r16]);
+      float lsum = 0.f, acc = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float f = exp2f(sm_m[w][r16] - m);
+        lsum = fmaf(sm_l[w][r16], f, lsum);
+        acc = fmaf(sm_o[w][r16][d], f, acc);
+      }
+      if (p.nsplit == 1) {
+        // The only range of this (request, KV head): finish here, no partials, no merge kernel.
+        const int t = rr / p.G, hq = g * p.G + rr % p.G;
+        p.out[((static_cast<size_t>(b) * p.T + t) * p.Hq + hq) * kD + d] = lsum > 0.f ? acc / lsum : 0.f;
+      } else {
+        p.part_o[(part + rr) * kD + d] = acc;
+        if (d == 0) p.part_ml[part + rr] = float2{m, lsum};
+      }
     }
   }
 }
@@ -408,7 +431,7 @@ extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* v
   SA_REQUIRE(D == kD && page_size == kPage, SA_EUNSUPPORTED, "%s: only D=128 and page_size=16 are built (D=%d, page_size=%d)",
              name, D, page_size);
   const int G = Hq / Hkv, R = T * G;
-  SA_REQUIRE(R <= 16, SA_EUNSUPPORTED, "%s: T*(Hq/Hkv)=%d exceeds the 16 query rows of one tile", name, R);
+  SA_REQUIRE(R <= 32, SA_EUNSUPPORTED, "%s: T*(Hq/Hkv)=%d exceeds the 32 query rows (two tiles) per KV head", name, R);
   const int rows = req_idx ? n_req : B;
   SA_REQUIRE(rows >= 0 && rows <= B, SA_EINVAL, "%s: n_req=%d outside [0,B=%d]", name, n_req, B);
   if (rows == 0) return SA_OK;
@@ -450,7 +473,10 @@ extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* v
   p.scale_log2 = scale * 1.4426950408889634f;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  sa::launch(SA_K_ATTN_SPLIT, attn_split_kernel, dim3(Hkv, sp.nsplit, rows), dim3(256), kOccupancyPadBytes, s, p);
+  if (R <= 16)
+    sa::launch(SA_K_ATTN_SPLIT, attn_split_kernel<1>, dim3(Hkv, sp.nsplit, rows), dim3(256), kOccupancyPadBytes, s, p);
+  else
+    sa::launch(SA_K_ATTN_SPLIT, attn_split_kernel<2>, dim3(Hkv, sp.nsplit, rows), dim3(256), kOccupancyPadBytes, s, p);
   sa_status st = sa::check_launch("attn_decode (split kernel)");
   if (st != SA_OK || sp.nsplit == 1) return st;
   sa::launch(SA_K_ATTN_MERGE, attn_merge_kernel, dim3(static_cast<unsigned>(rows * Hkv * R)), dim3(128), 0, s, p);

@@ -63,7 +63,7 @@ def _attn_call(**over):
 
 def test_attention_argument_errors():
     for bad, code in ((dict(D=64), sa.SA_EUNSUPPORTED), (dict(page_size=32), sa.SA_EUNSUPPORTED),
-                      (dict(T=5), sa.SA_EUNSUPPORTED), (dict(Hq=30), sa.SA_EINVAL), (dict(max_seq_len=65), sa.SA_EINVAL),
+                      (dict(T=9), sa.SA_EUNSUPPORTED), (dict(Hq=30), sa.SA_EINVAL), (dict(max_seq_len=65), sa.SA_EINVAL),
                       (dict(workspace_bytes=16), sa.SA_EWORKSPACE), (dict(kpool=None), sa.SA_EINVAL),
                       (dict(out=4), sa.SA_EINVAL), (dict(n_pages=0), sa.SA_EINVAL)):
         with pytest.raises(sa.SaError) as e:

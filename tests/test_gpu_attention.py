@@ -140,9 +140,10 @@ def test_append_then_attend_round_trip():
         assert rel_err(got, ref) <= OUT_TOL
 
 
-@pytest.mark.parametrize("hq,hkv,T", [(8, 8, 1), (8, 8, 8), (16, 8, 2), (24, 8, 3), (32, 4, 2), (16, 1, 1), (5, 5, 3)])
+@pytest.mark.parametrize("hq,hkv,T", [(8, 8, 1), (8, 8, 8), (16, 8, 2), (24, 8, 3), (32, 4, 2), (16, 1, 1), (5, 5, 3),
+                                       (32, 8, 8), (32, 8, 5), (16, 8, 12), (16, 1, 2)])
 def test_other_head_groupings_and_token_counts(hq, hkv, T):
-    """Group sizes 1..16 and 1..8 new tokens (up to 16 query rows per KV head), windowed and full."""
+    """Group sizes 1..16 and 1..8 new tokens (up to 32 query rows per KV head: one or two MFMA tiles), windowed and full."""
     lens = np.array([T + 3, 70, 555, 1300], dtype=np.int32)
     p = gen.attention_inputs(3060 + hq + T, len(lens), T, hq, hkv, D, lens, 96)
     klog, vlog = gen.logical_pools(p["k_tok"], p["v_tok"], p["page_table"], lens, p["n_pages"])
