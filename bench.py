@@ -215,7 +215,7 @@ def main():
         "metric": "mixer decode tokens/s at batch 64 + % of MI355X peak HBM GB/s",
         "value": round(B / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32 (bf16 operands and KV cache)",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "operand_dtype": "bf16 (q, k, v, KV cache); fp32 states, gates and outputs",
         "data": "synthetic",
         "config": {"workload": "batch-64 decode step through one GDN, one KDA, one FA (32768-token contexts) and one SWA "
                                "(w=4096, contexts U[8192,32768]) layer; 32 heads, 128x128 fp32 states, 32q/8kv heads, "
@@ -226,7 +226,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "placement48": placement,
-        "verify4": verify,
+        "verify": verify,
         "extras": extras,
     }
     print(json.dumps(line))
@@ -234,43 +234,43 @@ def main():
 
 def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_pages, lens_fa, lens_swa, rec_scale,
                 attn_scale, stream, alg, reps=6):
-    """Multi-token verify for self-speculative decoding: 4 drafted tokens per sequence scored in one pass
+    """Multi-token verify for self-speculative decoding: 4 and 8 drafted tokens per sequence scored in one pass
     of each mixer at the batch-64 shapes (same state / KV bytes as a single-token step)."""
-    T = 4
     res = {}
-    for name, kda, fn, kid in (("gdn", False, sa.gdn_decode_step, sa.SA_K_GDN), ("kda", True, sa.kda_decode_step, sa.SA_K_KDA)):
-        x = {n: dev(a) for n, a in gen.recurrent_inputs(1900 + kda, B, T, H, H, DK, DV, kda).items()}
-        states = rec[name][1]
-        out = torch.empty((B, T, H, DV), dtype=torch.float32, device="cuda")
-        sa.sa_prof_enable(True)
-        for i in range(reps):   # out of place: draft state kept, all 4 steps committed to the next set
-            fn(x["q"], x["k"], x["v"], x["alpha"], x["beta"], states[i % N_STATE_SETS], states[(i + 1) % N_STATE_SETS], out,
-               None, None, 0, B, T, H, H, DK, DV, rec_scale, T, stream)
-        torch.cuda.synchronize()
-        sa.sa_prof_enable(False)
-        _, _, ms = sa.sa_prof_read(kid, reps)
-        avg = sum(ms[1:]) / (len(ms) - 1)
-        nbytes = alg[name + "_decode_step"]
-        res[name + "_T4"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
-                             "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-    q4 = dev(gen.attention_inputs(1910, B, T, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"])
-    ws_bytes = max(sa.attn_decode_workspace_bytes(B, T, HQ, HKV, D, CTX, 0),
-                   sa.attn_decode_workspace_bytes(B, T, HQ, HKV, D, CTX, WINDOW))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    out = torch.empty((B, T, HQ, D), dtype=torch.float32, device="cuda")
-    for name, lens, window in (("fa", lens_fa, 0), ("swa", lens_swa, WINDOW)):
-        sa.sa_prof_enable(True)
-        for _ in range(reps):
-            sa.attn_decode(q4, kpool, vpool, n_pages, table, max_pages, lens, None, 0, out, B, T, HQ, HKV, D, PAGE, CTX, window,
-                           attn_scale, ws, ws_bytes, stream)
-        torch.cuda.synchronize()
-        sa.sa_prof_enable(False)
-        _, _, ms = sa.sa_prof_read(sa.SA_K_ATTN_SPLIT, reps)
-        sa.sa_prof_read(sa.SA_K_ATTN_MERGE, reps)
-        avg = sum(ms[1:]) / (len(ms) - 1)
-        nbytes = alg["attn_split_" + name]
-        res[name + "_T4"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
-                             "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    for T in (4, 8):
+        for name, kda, fn, kid in (("gdn", False, sa.gdn_decode_step, sa.SA_K_GDN), ("kda", True, sa.kda_decode_step, sa.SA_K_KDA)):
+            x = {n: dev(a) for n, a in gen.recurrent_inputs(1900 + kda + T, B, T, H, H, DK, DV, kda).items()}
+            states = rec[name][1]
+            out = torch.empty((B, T, H, DV), dtype=torch.float32, device="cuda")
+            sa.sa_prof_enable(True)
+            for i in range(reps):   # out of place: draft state kept, all T steps committed to the next set
+                fn(x["q"], x["k"], x["v"], x["alpha"], x["beta"], states[i % N_STATE_SETS], states[(i + 1) % N_STATE_SETS], out,
+                   None, None, 0, B, T, H, H, DK, DV, rec_scale, T, stream)
+            torch.cuda.synchronize()
+            sa.sa_prof_enable(False)
+            _, _, ms = sa.sa_prof_read(kid, reps)
+            avg = sum(ms[1:]) / (len(ms) - 1)
+            nbytes = alg[name + "_decode_step"]
+            res["%s_T%d" % (name, T)] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
+                                         "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        q = dev(gen.attention_inputs(1910 + T, B, T, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"])
+        ws_bytes = max(sa.attn_decode_workspace_bytes(B, T, HQ, HKV, D, CTX, 0),
+                       sa.attn_decode_workspace_bytes(B, T, HQ, HKV, D, CTX, WINDOW))
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        out = torch.empty((B, T, HQ, D), dtype=torch.float32, device="cuda")
+        for name, lens, window in (("fa", lens_fa, 0), ("swa", lens_swa, WINDOW)):
+            sa.sa_prof_enable(True)
+            for _ in range(reps):
+                sa.attn_decode(q, kpool, vpool, n_pages, table, max_pages, lens, None, 0, out, B, T, HQ, HKV, D, PAGE, CTX, window,
+                               attn_scale, ws, ws_bytes, stream)
+            torch.cuda.synchronize()
+            sa.sa_prof_enable(False)
+            _, _, ms = sa.sa_prof_read(sa.SA_K_ATTN_SPLIT, reps)
+            sa.sa_prof_read(sa.SA_K_ATTN_MERGE, reps)
+            avg = sum(ms[1:]) / (len(ms) - 1)
+            nbytes = alg["attn_split_" + name]
+            res["%s_T%d" % (name, T)] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
+                                         "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     return res
 
 
