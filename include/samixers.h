@@ -152,7 +152,8 @@ sa_status kv_append(const void* k_new, const void* v_new, void* kpool, void* vpo
  *
  *   q          bf16 [B,T,Hq,D]            out  fp32 [B,T,Hq,D]
  *   seq_lens   int32 [B]                  req_idx as for the recurrent mixers
- *   workspace  at least attn_decode_workspace_bytes(...) bytes, 16-byte aligned; holds the per-split
+ *   workspace  at least attn_decode_workspace_bytes(...) bytes (0 when the plan has a single page range per
+ *              (request, KV head); workspace may then be NULL), 16-byte aligned; holds the per-split
  *              partial results (running maximum, normaliser, unnormalised output) that a second
  *              kernel merges in a fixed order, so results are run-to-run deterministic.
  * Supported: D = 128, page_size = 16, T * (Hq/Hkv) <= 32 (e.g. 8 new tokens at 4 query heads per KV head).
@@ -207,8 +208,9 @@ void placement_plan_destroy(sa_plan* plan);
 /* Number of requests that run mixer `mixer` ('F','S','K','G') at layer `layer`; -1 on bad arguments. */
 int placement_plan_count(const sa_plan* plan, int layer, char mixer);
 size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, int T, int max_seq_len, int window);
-/* io: host array of L descriptors.  Enqueues, layer by layer, one launch per mixer present in that
- * layer over that mixer's request list.  Recurrent layers commit all T steps in place. */
+/* io: host array of L descriptors.  Checks the arguments of every launch of the stack first (nothing is
+ * enqueued if any is bad), then enqueues, layer by layer, one launch per mixer present in that layer over
+ * that mixer's request list.  Recurrent layers commit all T steps in place. */
 sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,
                            float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes, void* stream);
 

@@ -21,8 +21,6 @@
 // keeps that same row in the lane, so the whole online softmax is lane-local except for a 2-step
 // maximum over the 4 token groups.  Probabilities are split into two bf16 terms (p = hi + lo) so the
 // second product carries ~16 mantissa bits of p instead of 8.
-#include <cstdlib>
-
 #include "common.h"
 
 namespace {
@@ -84,18 +82,6 @@ SplitPlan plan_splits(int n_req, int Hkv, int T, int max_seq_len, int window) {
     sp.nsplit = static_cast<int>((max_pages + per - 1) / per);
     return sp;
   };
-  // SAMIXERS_ATTN_TARGET_GROUPS=<workgroups wanted per launch> bypasses the model below in tuning runs.
-  static const long long forced = [] {
-    const char* e = std::getenv("SAMIXERS_ATTN_TARGET_GROUPS");
-    long long v = e ? std::atoll(e) : 0;
-    return v > 0 ? v : 0LL;
-  }();
-  if (forced) {
-    long long want = (forced + pairs - 1) / pairs;
-    const long long most = (max_pages + 7) / 8;
-    want = want > most ? most : want;
-    return make(want < 1 ? 1 : want);
-  }
   // Cost model.  The K/V stream runs fastest with 2 workgroups per CU (see kOccupancyPadBytes), so a
   // launch of N equal workgroups takes about ceil(N / slots) rounds, slots = 2 * CUs; a workgroup costs
   // its pages plus a start-up (lengths, page ids, first page: three dependent memory latencies, about
@@ -409,7 +395,9 @@ __global__ __launch_bounds__(128) void kv_append_kernel(AppendParams p) {
   p.vpool[block + (((d >> 4) * 4 + (j >> 2)) * 16 + (d & 15)) * 4 + (j & 3)] = p.v_new[src];
 }
 
+// A single range per (request, KV head) writes the output directly and needs no partials.
 size_t workspace_need(int n_req, int Hkv, int R, const SplitPlan& sp) {
+  if (sp.nsplit == 1) return 0;
   size_t parts = static_cast<size_t>(n_req) * Hkv * sp.nsplit * R;
   return parts * kD * sizeof(float) + parts * sizeof(float2);
 }
@@ -422,11 +410,12 @@ extern "C" size_t attn_decode_workspace_bytes(int n_req, int T, int Hq, int Hkv,
   return workspace_need(n_req, Hkv, R, plan_splits(n_req, Hkv, T, max_seq_len, window));
 }
 
-extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* vpool, int n_pages,
-                                 const int32_t* page_table, int max_pages, const int32_t* seq_lens,
-                                 const int32_t* req_idx, int n_req, float* out, int B, int T, int Hq, int Hkv, int D,
-                                 int page_size, int max_seq_len, int window, float scale, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
+namespace {
+
+sa_status attn_decode_impl(bool dry_run, const void* q, const void* kpool, const void* vpool, int n_pages,
+                           const int32_t* page_table, int max_pages, const int32_t* seq_lens, const int32_t* req_idx,
+                           int n_req, float* out, int B, int T, int Hq, int Hkv, int D, int page_size, int max_seq_len,
+                           int window, float scale, void* workspace, size_t workspace_bytes, void* stream) {
   const char* name = "attn_decode";
   SA_REQUIRE(B >= 0 && T >= 1, SA_EINVAL, "%s: need B >= 0 and T >= 1 (B=%d, T=%d)", name, B, T);
   SA_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0, SA_EINVAL, "%s: Hq must be a positive multiple of Hkv", name);
@@ -440,15 +429,17 @@ extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* v
   SA_REQUIRE(n_pages >= 1 && max_pages >= 1 && max_seq_len >= 0, SA_EINVAL, "%s: n_pages, max_pages must be >= 1", name);
   SA_REQUIRE(static_cast<long long>(max_seq_len) <= static_cast<long long>(max_pages) * kPage, SA_EINVAL,
              "%s: max_seq_len=%d does not fit max_pages=%d", name, max_seq_len, max_pages);
-  SA_REQUIRE(q && kpool && vpool && page_table && seq_lens && out && workspace, SA_EINVAL, "%s: null pointer", name);
+  SA_REQUIRE(q && kpool && vpool && page_table && seq_lens && out, SA_EINVAL, "%s: null pointer", name);
   SA_REQUIRE(sa::aligned(q, 16) && sa::aligned(kpool, 16) && sa::aligned(vpool, 16) && sa::aligned(out, 16) &&
                  sa::aligned(workspace, 16) && sa::aligned(page_table, 4) && sa::aligned(seq_lens, 4) &&
                  sa::aligned(req_idx, 4),
              SA_EINVAL, "%s: misaligned pointer", name);
   const SplitPlan sp = plan_splits(rows, Hkv, T, max_seq_len, window);
   const size_t need = workspace_need(rows, Hkv, R, sp);
+  SA_REQUIRE(need == 0 || workspace, SA_EINVAL, "%s: workspace is null", name);
   SA_REQUIRE(workspace_bytes >= need, SA_EWORKSPACE, "%s: workspace has %zu bytes, %zu needed", name, workspace_bytes, need);
   SA_REQUIRE(rows <= 65535 && Hkv <= 65535, SA_EUNSUPPORTED, "%s: more than 65535 rows or KV heads per launch", name);
+  if (dry_run) return SA_OK;
 
   AttnParams p;
   p.q = static_cast<const uint16_t*>(q);
@@ -483,6 +474,26 @@ extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* v
   if (st != SA_OK || sp.nsplit == 1) return st;
   sa::launch(SA_K_ATTN_MERGE, attn_merge_kernel, dim3(static_cast<unsigned>(rows * Hkv * R)), dim3(128), 0, s, p);
   return sa::check_launch("attn_decode (merge kernel)");
+}
+
+}  // namespace
+
+extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* vpool, int n_pages,
+                                 const int32_t* page_table, int max_pages, const int32_t* seq_lens,
+                                 const int32_t* req_idx, int n_req, float* out, int B, int T, int Hq, int Hkv, int D,
+                                 int page_size, int max_seq_len, int window, float scale, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  return attn_decode_impl(false, q, kpool, vpool, n_pages, page_table, max_pages, seq_lens, req_idx, n_req, out, B, T, Hq, Hkv, D,
+                          page_size, max_seq_len, window, scale, workspace, workspace_bytes, stream);
+}
+
+// Argument check of an attention launch without enqueueing anything.
+sa_status sa::check_attn_decode(const void* q, const void* kpool, const void* vpool, int n_pages, const int32_t* page_table,
+                                int max_pages, const int32_t* seq_lens, const int32_t* req_idx, int n_req, float* out, int B,
+                                int T, int Hq, int Hkv, int D, int page_size, int max_seq_len, int window, void* workspace,
+                                size_t workspace_bytes) {
+  return attn_decode_impl(true, q, kpool, vpool, n_pages, page_table, max_pages, seq_lens, req_idx, n_req, out, B, T, Hq, Hkv, D,
+                          page_size, max_seq_len, window, 1.f, workspace, workspace_bytes, nullptr);
 }
 
 extern "C" sa_status kv_append(const void* k_new, const void* v_new, void* kpool, void* vpool, int n_pages,

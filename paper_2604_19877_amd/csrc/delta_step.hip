@@ -205,7 +205,7 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
 }
 
 template <bool KDA>
-sa_status launch(const char* name, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+sa_status step_launch(bool dry_run, const char* name, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                  const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
                  int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream) {
   SA_REQUIRE(B >= 0 && T >= 1 && T <= 8, SA_EINVAL, "%s: need B >= 0 and 1 <= T <= 8 (B=%d, T=%d)", name, B, T);
@@ -222,6 +222,7 @@ sa_status launch(const char* name, const void* q, const void* k, const void* v, 
                  sa::aligned(beta, 4) && sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4),
              SA_EINVAL, "%s: misaligned pointer", name);
   SA_REQUIRE(static_cast<long long>(rows) * H <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many tiles", name);
+  if (dry_run) return SA_OK;
 
   DeltaParams p{static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                 alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale, n_commit};
@@ -246,7 +247,7 @@ extern "C" sa_status gdn_decode_step(const void* q, const void* k, const void* v
                                      const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
                                      float scale, int n_commit, void* stream) {
-  return launch<false>("gdn_decode_step", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B,
+  return step_launch<false>(false, "gdn_decode_step", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B,
                        T, H, Hk, dk, dv, scale, n_commit, stream);
 }
 
@@ -254,6 +255,18 @@ extern "C" sa_status kda_decode_step(const void* q, const void* k, const void* v
                                      const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
                                      float scale, int n_commit, void* stream) {
-  return launch<true>("kda_decode_step", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T,
+  return step_launch<true>(false, "kda_decode_step", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T,
                       H, Hk, dk, dv, scale, n_commit, stream);
+}
+
+// Argument check of a recurrent step without enqueueing anything (used by placement_decode to validate a
+// whole stack before its first launch).
+sa_status sa::check_recurrent_step(bool kda, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                                   const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                                   const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, int n_commit) {
+  if (kda)
+    return step_launch<true>(true, "kda_decode_step", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
+                        Hk, dk, dv, 1.f, n_commit, nullptr);
+  return step_launch<false>(true, "gdn_decode_step", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
+                       Hk, dk, dv, 1.f, n_commit, nullptr);
 }

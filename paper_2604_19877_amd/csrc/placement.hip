@@ -110,25 +110,40 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
   SA_REQUIRE(static_cast<long long>(sh->H) * sh->dv == static_cast<long long>(sh->Hq) * sh->D, SA_EINVAL,
              "%s: H*dv must equal Hq*D so that all mixers share the output rows", name);
   const int B = plan->B;
-  for (int l = 0; l < plan->L; ++l) {
-    const sa_layer_io& x = io[l];
-    for (int m = 0; m < 4; ++m) {
-      const int n = plan->counts[l * 4 + m];
-      if (n == 0) continue;
-      const int32_t* list = plan->dev_lists + plan->offsets[l * 4 + m];
-      sa_status st;
-      if (m == 0 || m == 1) {
-        st = attn_decode(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, list, n, x.out, B,
-                         T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, m == 0 ? 0 : window, attn_scale,
-                         workspace, workspace_bytes, stream);
-      } else if (m == 2) {
-        st = kda_decode_step(x.q, x.k, x.v, x.alpha_vec, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T,
-                             sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, stream);
-      } else {
-        st = gdn_decode_step(x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T,
-                             sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, stream);
+  // Two passes over the stack: the first only checks every launch's arguments, so that a bad descriptor
+  // anywhere is reported before anything has been enqueued.
+  for (int pass = 0; pass < 2; ++pass) {
+    const bool check = pass == 0;
+    for (int l = 0; l < plan->L; ++l) {
+      const sa_layer_io& x = io[l];
+      for (int m = 0; m < 4; ++m) {
+        const int n = plan->counts[l * 4 + m];
+        if (n == 0) continue;
+        const int32_t* list = plan->dev_lists + plan->offsets[l * 4 + m];
+        sa_status st;
+        if (m == 0 || m == 1) {
+          const int w = m == 0 ? 0 : window;
+          st = check ? sa::check_attn_decode(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, list, n,
+                                             x.out, B, T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, w, workspace,
+                                             workspace_bytes)
+                     : attn_decode(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, list, n, x.out, B,
+                                   T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, w, attn_scale, workspace,
+                                   workspace_bytes, stream);
+        } else {
+          const bool kda = m == 2;
+          const float* alpha = kda ? x.alpha_vec : x.alpha_scalar;
+          if (check)
+            st = sa::check_recurrent_step(kda, x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T,
+                                          sh->H, sh->Hk, sh->dk, sh->dv, T);
+          else if (kda)
+            st = kda_decode_step(x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T, sh->H, sh->Hk,
+                                 sh->dk, sh->dv, rec_scale, T, stream);
+          else
+            st = gdn_decode_step(x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T, sh->H, sh->Hk,
+                                 sh->dk, sh->dv, rec_scale, T, stream);
+        }
+        if (st != SA_OK) return st;
       }
-      if (st != SA_OK) return st;
     }
   }
   return SA_OK;

@@ -164,3 +164,32 @@ def test_full_size_stack_batch128_ctx16384_sampled():
                     assert rel_err(got[:, h], ref[0, :, 0]) <= OUT_TOL, (l, r, m, h)
     finally:
         w.close()
+
+
+def test_bad_descriptor_in_the_last_layer_enqueues_nothing():
+    """Every launch of the stack is checked before the first one is enqueued."""
+    L, B, ctx, window, max_pages = 3, 2, 100, 64, 8
+    layers = build_stack(5300, L, B, 1, ctx, max_pages)
+    plan = sa.placement_plan_create(["FGK"], np.zeros(B, dtype=np.int32))
+    shapes = sa.sa_shapes(H, H, DK, DV, HQ, HKV, D, 16)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    keep, ios = [], []
+    for l, io in enumerate(layers):
+        kphys, vphys = kl.to_physical(io["kpool"], io["vpool"])
+        t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
+        t["state"], t["kpool"], t["vpool"] = dev(io["state"].copy()), dev(kphys), dev(vphys)
+        t["out"] = torch.full((B, 1, H, DV), 55.0, dtype=torch.float32, device="cuda")
+        keep.append(t)
+        ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"],
+                                    alpha_vec=None if l == L - 1 else t["alpha_vec"],          # the KDA layer lacks its gate
+                                    beta=t["beta"], state=t["state"], q_attn=t["qa"], kpool=t["kpool"], vpool=t["vpool"],
+                                    n_pages=io["n_pages"], page_table=t["page_table"], seq_lens=t["seq_lens"],
+                                    max_pages=max_pages, max_seq_len=ctx, out=t["out"]))
+    with pytest.raises(sa.SaError) as e:
+        sa.placement_decode(plan, ios, shapes, 1, window, 1.0, 1.0, ws, ws.numel())
+    assert e.value.status == sa.SA_EINVAL and "kda_decode_step" in str(e.value)
+    torch.cuda.synchronize()
+    for l, t in enumerate(keep):
+        assert (t["out"] == 55.0).all()
+        assert np.array_equal(host(t["state"]), layers[l]["state"])
+    sa.placement_plan_destroy(plan)
