@@ -61,7 +61,7 @@ int sa_version(void);
  *   slot_idx  int32 [B] or NULL: batch row -> state slot (NULL = identity)
  *   req_idx   int32 [n_req] or NULL: the batch rows to process (NULL = rows 0..B-1, n_req ignored);
  *             rows not listed are not touched.  A row must not be listed twice.
- * Supported: (dk,dv) in {(64,64),(128,128)}, 1 <= T <= 8.  B = 0 or n_req = 0 is a no-op.
+ * Supported: (dk,dv) in {(64,64),(128,128)}, 1 <= T <= 16.  B = 0 or n_req = 0 is a no-op.
  */
 sa_status gdn_decode_step(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                           const float* state_in, float* state_out, float* out,

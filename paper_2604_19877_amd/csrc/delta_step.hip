@@ -208,7 +208,7 @@ template <bool KDA>
 sa_status step_launch(bool dry_run, const char* name, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                  const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
                  int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream) {
-  SA_REQUIRE(B >= 0 && T >= 1 && T <= 8, SA_EINVAL, "%s: need B >= 0 and 1 <= T <= 8 (B=%d, T=%d)", name, B, T);
+  SA_REQUIRE(B >= 0 && T >= 1 && T <= 16, SA_EINVAL, "%s: need B >= 0 and 1 <= T <= 16 (B=%d, T=%d)", name, B, T);
   SA_REQUIRE(H >= 1 && Hk >= 1 && H % Hk == 0, SA_EINVAL, "%s: H must be a positive multiple of Hk (H=%d, Hk=%d)", name, H, Hk);
   SA_REQUIRE(n_commit >= 0 && n_commit <= T, SA_EINVAL, "%s: n_commit=%d outside [0,T=%d]", name, n_commit, T);
   SA_REQUIRE((dk == 64 && dv == 64) || (dk == 128 && dv == 128), SA_EUNSUPPORTED,

@@ -44,7 +44,7 @@ def test_recurrent_argument_errors(fn):
     with pytest.raises(sa.SaError) as e:
         _recurrent_call(fn, dk=96, dv=96)
     assert e.value.status == sa.SA_EUNSUPPORTED and "96" in str(e.value)
-    for bad in (dict(T=0), dict(T=9), dict(Hk=3), dict(n_commit=2), dict(n_commit=-1), dict(q=None), dict(state_out=8),
+    for bad in (dict(T=0), dict(T=17), dict(Hk=3), dict(n_commit=2), dict(n_commit=-1), dict(q=None), dict(state_out=8),
                 dict(req_idx=16, n_req=3)):
         with pytest.raises(sa.SaError) as e:
             _recurrent_call(fn, **bad)

@@ -42,9 +42,9 @@ def run_gpu(kda, p, state0, B, T, H, Hk, dk, dv, scale):
 
 
 @pytest.mark.parametrize("kda", [False, True])
-@pytest.mark.parametrize("T", [1, 8])
+@pytest.mark.parametrize("T", [1, 8, 16])
 def test_config1_256_tokens_from_zero_state(kda, T):
-    """B=2, H=4, dk=dv=64, 256 tokens, zero initial state; fed one token per call and 8 per call."""
+    """B=2, H=4, dk=dv=64, 256 tokens, zero initial state; fed 1, 8 and 16 tokens per call."""
     B, H, dk, dv, n_tok = 2, 4, 64, 64, 256
     p = stepwise_inputs(1001 + kda, n_tok // T, B, T, H, H, dk, dv, kda)
     S0 = np.zeros((B, H, dk, dv), dtype=np.float32)
