@@ -73,6 +73,20 @@ sa_status kda_decode_step(const void* q, const void* k, const void* v, const flo
                           int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Many tokens per state pass: the same recurrence and read-out as gdn_decode_step, evaluated in its
+ * chunk-parallel form (Appendix B: GDN runs "chunkwise" on a WY representation; Section 6: chunkwise
+ * kernels serve prefill).  Tokens are processed 16 at a time as matrix products on the matrix cores with the
+ * state held in registers across the whole call; results equal T chained single steps to fp32 rounding
+ * (every fp32 operand of a product is split exactly into three bf16 terms).  Arguments as for
+ * gdn_decode_step; any T >= 1; the state written is always the one after all T tokens (use gdn_decode_step
+ * with n_commit for a roll-back).  Supported: (dk,dv) = (128,128).
+ */
+sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                          const float* state_in, float* state_out, float* out,
+                          const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                          int B, int T, int H, int Hk, int dk, int dv, float scale, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Whole-block decode step of a recurrent mixer: the state update above with the block's own pre- and
  * post-processing fused around it in one launch (Appendix B: a short causal 1-D convolution with SiLU on
  * Q, K and V, L2-normalised q and k, beta = sigmoid(beta_raw), log-decay
@@ -256,7 +270,7 @@ sa_status sa_pool_layer_tables(const sa_pool* pool, const int32_t* seq_ids, int 
  * Measurement helpers (not part of the method).
  */
 enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5,
-       SA_K_GDN_BLOCK = 6, SA_K_KDA_BLOCK = 7, SA_K_COUNT = 8 };
+       SA_K_GDN_BLOCK = 6, SA_K_KDA_BLOCK = 7, SA_K_GDN_CHUNK = 8, SA_K_KDA_CHUNK = 9, SA_K_COUNT = 10 };
 /* While enabled, every launch of the kernels above carries HIP start/stop events on its stream that
  * are stamped with the begin and end of the kernel itself. */
 void sa_prof_enable(int on);

@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsamixers.so")
 
 SA_OK, SA_EINVAL, SA_EUNSUPPORTED, SA_EHIP, SA_EWORKSPACE, SA_ENOMEM = 0, -1, -2, -3, -4, -5
-SA_K_GDN, SA_K_KDA, SA_K_ATTN_SPLIT, SA_K_ATTN_MERGE, SA_K_KV_APPEND, SA_K_COPY, SA_K_GDN_BLOCK, SA_K_KDA_BLOCK = range(8)
+(SA_K_GDN, SA_K_KDA, SA_K_ATTN_SPLIT, SA_K_ATTN_MERGE, SA_K_KV_APPEND, SA_K_COPY, SA_K_GDN_BLOCK, SA_K_KDA_BLOCK,
+ SA_K_GDN_CHUNK, SA_K_KDA_CHUNK) = range(10)
 
 
 class SaError(RuntimeError):
@@ -47,11 +48,13 @@ class sa_block_io(ctypes.Structure):
 
 _BLOCK_ARGS = [ctypes.POINTER(sa_block_io)] + [c_void_p] * 5 + [c_int] * 6 + [c_float, c_void_p]
 _RECURRENT_ARGS = [c_void_p] * 10 + [c_int] * 7 + [c_float, c_int, c_void_p]
+_CHUNK_ARGS = [c_void_p] * 10 + [c_int] * 7 + [c_float, c_void_p]
 _SIGNATURES = {
     "sa_last_error": (c_char_p, []),
     "sa_version": (c_int, []),
     "gdn_decode_step": (c_int, _RECURRENT_ARGS),
     "kda_decode_step": (c_int, _RECURRENT_ARGS),
+    "gdn_chunk_steps": (c_int, _CHUNK_ARGS),
     "gdn_block_decode": (c_int, _BLOCK_ARGS),
     "kda_block_decode": (c_int, _BLOCK_ARGS),
     "kv_append": (c_int, [c_void_p] * 4 + [c_int, c_void_p, c_int, c_void_p] + [c_int] * 5 + [c_void_p]),
@@ -149,6 +152,13 @@ def kda_decode_step(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, re
                     n_commit, stream=None):
     _recurrent(lib().kda_decode_step, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
                Hk, dk, dv, scale, n_commit, stream)
+
+
+def gdn_chunk_steps(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,
+                    stream=None):
+    _check(lib().gdn_chunk_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), _ptr(state_in), _ptr(state_out),
+                                 _ptr(out), _ptr(slot_idx), _ptr(req_idx), n_req, B, T, H, Hk, dk, dv, scale,
+                                 _stream(stream)))
 
 
 def make_block_io(**kw):

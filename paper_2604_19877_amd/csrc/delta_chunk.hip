@@ -1,0 +1,394 @@
+// Chunk-parallel form of the GDN recurrence on the matrix cores, gfx950: many tokens per state pass.
+//
+// Appendix B of the paper says GDN runs "chunkwise" on a WY representation for long inputs and
+// Section 6 uses such kernels for prefill; the paper prints only the token-by-token recurrence
+//     S_t = alpha_t (I - beta_t k_t k_t^T) S_{t-1} + beta_t k_t v_t^T,      o_t = scale S_t^T q_t.
+// Unrolled over a chunk of C = 16 tokens with g(t,i) = prod_{i<m<=t} alpha_m  (g(t,t) = 1,
+// g(t,-1) = the decay from the chunk's start through step t):
+//     S_t      = g(t,-1) S_0 + sum_{i<=t} g(t,i) k_i delta_i^T
+//     delta_t  = beta_t (v_t - g(t,-1) S_0^T k_t) - sum_{i<t} beta_t g(t,i) (k_t.k_i) delta_i
+//     o_t      = scale ( g(t,-1) S_0^T q_t + sum_{i<=t} g(t,i) (q_t.k_i) delta_i )
+// so a chunk costs three state-sized matrix products (K S_0, Q S_0, K^T Delta), two 16x16 Gram
+// matrices, and one unit-lower-triangular solve with 16 unknown rows.
+//
+// Precision.  States are fp32 and must stay within 1e-4 of the fp64 recurrence after hundreds of
+// steps, so nothing fp32 is rounded to one bf16: every fp32 operand of a matrix product is split into
+// several bf16 terms and the product is the sum of one bf16 MFMA per term with fp32 accumulation:
+// the corrections delta, which are added to the state, into three truncated terms (8 + 8 + 8
+// significant bits, exact); the state as an operand of K S_0 and Q S_0 into two rounded terms
+// (relative error 2^-18, unbiased; it reaches the state only through delta).  q, k arrive as bf16
+// and are used as they are.  The decay factors are applied in fp32 outside the products, as
+// 2^(difference of running sums of log2 alpha), which never exceeds 1 (no division, no overflow
+// for any alpha in (0,1]).
+//
+// Work split.  As in the one-token kernel, value columns are independent: a workgroup owns one
+// (sequence, head) tile, each of its 4 wavefronts 32 value columns and all 128 key rows.  The
+// state lives in registers in the MFMA accumulator layout for the whole call: lane (n = lane%16,
+// g = lane/16) holds key rows 16r+4g .. 16r+4g+3 (r = 0..7) of columns 32w+2n and 32w+2n+1.
+// That layout is at once the C/D layout of K^T Delta (so the update accumulates in place), the
+// B-operand layout of the 16x16x16 product, and - two row tiles side by side, with the A operand
+// permuted to match - the B operand of the 16x16x32 product used for K S_0 and Q S_0.
+// The workgroup stages each chunk's K and Q in LDS once (token-major for the A operands of
+// K S_0 / Q S_0 and the Gram matrices, channel-major for the A operand of K^T Delta), double
+// buffered with one barrier per chunk.  Each wavefront solves the triangular system for its own
+// columns in four 4-row stages: rows live 4 to a lane, so a stage is a 4x4 solve inside the lanes
+// of one group, a broadcast of its 4 results, and a 4x4 block update in the later groups.
+#include "common.h"
+#include "delta_device.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+struct ChunkParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  const float* alpha;
+  const float* beta;
+  const float* state_in;
+  float* state_out;
+  float* out;
+  const int32_t* slot_idx;
+  const int32_t* req_idx;
+  int T, H, Hk;
+  float scale;
+};
+
+constexpr int kD = 128;          // dk = dv
+constexpr int kC = 16;           // tokens per chunk
+constexpr int kTokRowB = 272;    // bytes of one token row of K or Q in LDS (256 + 16: spreads the rows over banks)
+constexpr int kChRowB = 40;      // bytes of one key-channel row (16 tokens, 32 + 8) of the channel-major K copy
+constexpr int kStageB = 2 * kC * kTokRowB + kD * kChRowB;  // one chunk's K, Q and transposed K
+constexpr int kMatRow = 20;      // floats per row of the per-wavefront 16x16 matrices (16 + 4)
+constexpr int kWaveB = (2 * kC * kMatRow + kC * 4) * 4;     // A (off-diagonal blocks), M, diagonal blocks of A
+
+// Top 16 bits of two floats as one packed bf16 pair (element 0 in the low half): truncation.
+__device__ __forceinline__ uint32_t pack_trunc(float lo, float hi) {
+  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+__device__ __forceinline__ float trunc_bf16(float x) { return __uint_as_float(__float_as_uint(x) & 0xffff0000u); }
+
+// Exact three-way split of 4 floats (one accumulator tile row group) into bf16 quadruples.
+struct Split4 {
+  u32x2 hi, mid, lo;
+};
+__device__ __forceinline__ Split4 split3(const f32x4& x) {
+  Split4 s;
+  float r[4], r2[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) r[e] = x[e] - trunc_bf16(x[e]);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) r2[e] = r[e] - trunc_bf16(r[e]);
+  s.hi = u32x2{pack_trunc(x[0], x[1]), pack_trunc(x[2], x[3])};
+  s.mid = u32x2{pack_trunc(r[0], r[1]), pack_trunc(r[2], r[3])};
+  s.lo = u32x2{pack_trunc(r2[0], r2[1]), pack_trunc(r2[2], r2[3])};
+  return s;
+}
+// Two-term split with round-to-nearest in both terms: x = hi + lo up to 2^-18 |x|.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ uint32_t pack_rne(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+struct Split4x2 {
+  u32x2 hi, lo;
+};
+__device__ __forceinline__ Split4x2 split2(const f32x4& x) {
+  Split4x2 s;
+  s.hi = u32x2{pack_rne(x[0], x[1]), pack_rne(x[2], x[3])};
+  const float r0 = x[0] - bf16_lo(s.hi[0]), r1 = x[1] - bf16_hi(s.hi[0]);
+  const float r2 = x[2] - bf16_lo(s.hi[1]), r3 = x[3] - bf16_hi(s.hi[1]);
+  s.lo = u32x2{pack_rne(r0, r1), pack_rne(r2, r3)};
+  return s;
+}
+__device__ __forceinline__ bf16x8 join8(const u32x2& a, const u32x2& b) {
+  return __builtin_bit_cast(bf16x8, u32x4{a[0], a[1], b[0], b[1]});
+}
+
+// Orders this wavefront's LDS writes before its later LDS reads by other lanes.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// What a thread fetches from global memory for one chunk.
+struct ChunkFetch {
+  u32x4 kst, qst;     // staging: 8 channels of one token of K and of Q
+  uint32_t v[4];      // this lane's two value columns of tokens 4g .. 4g+3
+  float alpha, beta;  // of token lane%16
+};
+
+__device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p, size_t row0, int t0, int h, int hk, int col,
+                                            int g, int n) {
+  const int tid = threadIdx.x;
+  const int tok = tid >> 4, c8 = (tid & 15) * 8;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  f.kst = zero;
+  f.qst = zero;
+  if (t0 + tok < p.T) {
+    const size_t at = ((row0 + t0 + tok) * p.Hk + hk) * kD + c8;
+    f.kst = *reinterpret_cast<const u32x4*>(p.k + at);
+    f.qst = *reinterpret_cast<const u32x4*>(p.q + at);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int t = t0 + 4 * g + j;
+    f.v[j] = t < p.T ? *reinterpret_cast<const uint32_t*>(p.v + ((row0 + t) * p.H + h) * kD + col) : 0u;
+  }
+  const int tn = t0 + n;
+  f.alpha = tn < p.T ? p.alpha[(row0 + tn) * p.H + h] : 1.f;
+  f.beta = tn < p.T ? p.beta[(row0 + tn) * p.H + h] : 0.f;
+}
+
+__global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int r = blockIdx.x / p.H;
+  const int h = blockIdx.x - r * p.H;
+  const int b = p.req_idx ? p.req_idx[r] : r;
+  const int slot = p.slot_idx ? p.slot_idx[b] : b;
+  const int hk = h / (p.H / p.Hk);
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int n = lane & 15, g = lane >> 4;
+  const int col = wave * 32 + 2 * n;
+  const size_t row0 = static_cast<size_t>(b) * p.T;
+
+  float* const wave_mat = reinterpret_cast<float*>(lds + 2 * kStageB + wave * kWaveB);
+  float* const a_off = wave_mat;                      // [16][kMatRow]: beta_t g(t,i) k_t.k_i for i in an earlier 4-row group
+  float* const m_low = wave_mat + kC * kMatRow;       // [16][kMatRow]: g(t,i) q_t.k_i for i <= t
+  float* const a_dia = wave_mat + 2 * kC * kMatRow;   // [16][4]: the same products for i in t's own group, i < t
+
+  // Uniform tile base plus a 32-bit lane offset, so that addresses cost one register each.
+  const size_t tile = (static_cast<size_t>(slot) * p.H + h) * (kD * kD);
+  const float* const sin = p.state_in + tile;
+  float* const sout = p.state_out + tile;
+  const uint32_t lane_off = static_cast<uint32_t>(4 * g * kD + col);
+
+  ChunkFetch cur, nxt;
+  fetch_chunk(cur, p, row0, 0, h, hk, col, g, n);
+  // S[rt][c][j]: key row 16 rt + 4 g + j, value column col + c.
+  f32x4 S[8][2];
+#pragma unroll
+  for (int rt = 0; rt < 8; ++rt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x2 x = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sin + (lane_off + (16 * rt + j) * kD)));
+      S[rt][0][j] = x[0];
+      S[rt][1][j] = x[1];
+    }
+  __builtin_amdgcn_sched_barrier(0);
+
+  const int n_chunks = (p.T + kC - 1) / kC;
+  for (int ch = 0; ch < n_chunks; ++ch) {
+    const int t0 = ch * kC;
+    unsigned char* const stage = lds + (ch & 1) * kStageB;
+    unsigned char* const k_tok = stage;                       // [16 tokens][kTokRowB]
+    unsigned char* const q_tok = stage + kC * kTokRowB;
+    unsigned char* const k_chn = stage + 2 * kC * kTokRowB;   // [128 channels][kChRowB]
+    {
+      const int tok = tid >> 4, c8 = (tid & 15) * 8;
+      *reinterpret_cast<u32x4*>(k_tok + tok * kTokRowB + c8 * 2) = cur.kst;
+      *reinterpret_cast<u32x4*>(q_tok + tok * kTokRowB + c8 * 2) = cur.qst;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t w = cur.kst[e >> 1];
+        *reinterpret_cast<uint16_t*>(k_chn + (c8 + e) * kChRowB + tok * 2) = static_cast<uint16_t>((e & 1) ? (w >> 16) : (w & 0xffffu));
+      }
+    }
+    __syncthreads();
+    // The buffer written above was last read two chunks ago, and every wavefront has passed the
+    // previous chunk's barrier since, so one barrier per chunk is enough.
+    if (ch + 1 < n_chunks) fetch_chunk(nxt, p, row0, t0 + kC, h, hk, col, g, n);
+
+    // A operands of the 16x16x32 products: token n, key rows {32s+4g..+3, 32s+16+4g..+3}, the same
+    // rows as a pair of state tiles holds in this lane.
+    bf16x8 kf[4], qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int off = n * kTokRowB + (32 * s + 4 * g) * 2;
+      kf[s] = join8(*reinterpret_cast<const u32x2*>(k_tok + off), *reinterpret_cast<const u32x2*>(k_tok + off + 32));
+      qf[s] = join8(*reinterpret_cast<const u32x2*>(q_tok + off), *reinterpret_cast<const u32x2*>(q_tok + off + 32));
+    }
+
+    // Gram matrices: lane (n, g) gets k_t.k_n and q_t.k_n for t = 4g+j.
+    f32x4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s], kf[s], kk, 0, 0, 0);
+      qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], kf[s], qk, 0, 0, 0);
+    }
+
+    // Decay factors from the running sum of log2(alpha): every g(t,i) = 2^(L_t - L_i) is at most 1, so no
+    // product of gates can overflow or divide by an underflowed one.  Every lane holds alpha and beta of
+    // token lane%16; a gate below the smallest normal number acts as that number.
+    float log_sum = log2f(fmaxf(cur.alpha, 1.17549435e-38f));  // inclusive prefix sum L_n
+#pragma unroll
+    for (int d = 1; d < 16; d *= 2) {
+      const float y = __shfl_up(log_sum, d, 16);
+      if (n >= d) log_sum += y;
+    }
+    const float log_chunk = __shfl(log_sum, 15);
+    float g_start[4], g_end[4], beta_t[4], ratio[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float lt = __shfl(log_sum, 4 * g + j);
+      g_start[j] = exp2f(lt);
+      g_end[j] = exp2f(log_chunk - lt);
+      ratio[j] = exp2f(fminf(lt - log_sum, 0.f));  // g(t,n) for t = 4g+j >= n (unused otherwise)
+      beta_t[j] = __shfl(cur.beta, 4 * g + j);
+    }
+    const float g_chunk = exp2f(log_chunk);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = 4 * g + j;
+      const float a = n < t ? beta_t[j] * ratio[j] * kk[j] : 0.f;
+      a_off[t * kMatRow + n] = (n >> 2) < g ? a : 0.f;
+      if ((n >> 2) == g) a_dia[t * 4 + (n & 3)] = a;
+      m_low[t * kMatRow + n] = n <= t ? ratio[j] * qk[j] : 0.f;
+    }
+    wave_lds_sync();
+
+    // K S_0 and Q S_0 for this wavefront's 32 columns (rows = tokens 4g+j).
+    f32x4 u[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, w[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const Split4x2 lo_tile = split2(S[2 * s][c]), hi_tile = split2(S[2 * s + 1][c]);
+        const bf16x8 b_hi = join8(lo_tile.hi, hi_tile.hi), b_lo = join8(lo_tile.lo, hi_tile.lo);
+        u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s], b_lo, u[c], 0, 0, 0);
+        w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], b_lo, w[c], 0, 0, 0);
+        u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s], b_hi, u[c], 0, 0, 0);
+        w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], b_hi, w[c], 0, 0, 0);
+      }
+
+    // Right-hand sides and the state's share of the read-out.
+    f32x4 rhs[2], o[2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      rhs[0][j] = beta_t[j] * (bf16_lo(cur.v[j]) - g_start[j] * u[0][j]);
+      rhs[1][j] = beta_t[j] * (bf16_hi(cur.v[j]) - g_start[j] * u[1][j]);
+      o[0][j] = g_start[j] * w[0][j];
+      o[1][j] = g_start[j] * w[1][j];
+    }
+
+    // Forward substitution by 4-row groups; rhs turns into delta in place.
+    const f32x4 dia1 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 1) * 4);
+    const f32x4 dia2 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 2) * 4);
+    const f32x4 dia3 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 3) * 4);
+#pragma unroll
+    for (int gp = 0; gp < 4; ++gp) {
+      if (g == gp) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          rhs[c][1] -= dia1[0] * rhs[c][0];
+          rhs[c][2] -= dia2[0] * rhs[c][0] + dia2[1] * rhs[c][1];
+          rhs[c][3] -= dia3[0] * rhs[c][0] + dia3[1] * rhs[c][1] + dia3[2] * rhs[c][2];
+        }
+      }
+      if (gp == 3) break;  // nothing follows the last group
+      float d[2][4];
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) d[c][jp] = __shfl(rhs[c][jp], 16 * gp + n);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(a_off + (4 * g + j) * kMatRow + 4 * gp);
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int jp = 0; jp < 4; ++jp) rhs[c][j] = fmaf(-a[jp], d[c][jp], rhs[c][j]);
+      }
+    }
+
+    // Read-out: o += M Delta on the matrix cores.  This product only reaches the output (tolerance
+    // 2e-3), so two rounded terms per operand and the three leading cross products are plenty.
+    {
+      const Split4x2 ms = split2(*reinterpret_cast<const f32x4*>(m_low + n * kMatRow + 4 * g));  // A operand: row n, columns 4g..
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const Split4x2 dl = split2(rhs[c]);
+        o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.lo), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
+        o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.lo), o[c], 0, 0, 0);
+        o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
+      }
+    }
+
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = t0 + 4 * g + j;
+      if (t < p.T) {
+        const f32x2 y = {p.scale * o[0][j], p.scale * o[1][j]};
+        *reinterpret_cast<f32x2*>(p.out + ((row0 + t) * p.H + h) * kD + col) = y;
+      }
+    }
+
+    // S <- g(15,-1) S + K^T (g(15,t) delta_t): rows of the B operand are tokens.
+    Split4 ds[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      f32x4 x;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[j] = g_end[j] * rhs[c][j];
+      ds[c] = split3(x);
+    }
+#pragma unroll
+    for (int rt = 0; rt < 8; ++rt) {
+      const s16x4 kt = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g));
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        f32x4 acc = S[rt][c];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] *= g_chunk;
+        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].lo), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].mid), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].hi), acc, 0, 0, 0);
+        S[rt][c] = acc;
+      }
+    }
+    cur = nxt;
+    // The per-wavefront matrices are rewritten in the next chunk only after this chunk's reads (program order).
+  }
+
+#pragma unroll
+  for (int rt = 0; rt < 8; ++rt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x2 x = {S[rt][0][j], S[rt][1][j]};
+      __builtin_nontemporal_store(x, reinterpret_cast<f32x2*>(sout + (lane_off + (16 * rt + j) * kD)));
+    }
+}
+
+}  // namespace
+
+extern "C" sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                                     const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                                     const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
+                                     float scale, void* stream) {
+  const char* name = "gdn_chunk_steps";
+  SA_REQUIRE(B >= 0 && T >= 1, SA_EINVAL, "%s: need B >= 0 and T >= 1 (B=%d, T=%d)", name, B, T);
+  SA_REQUIRE(H >= 1 && Hk >= 1 && H % Hk == 0, SA_EINVAL, "%s: H must be a positive multiple of Hk (H=%d, Hk=%d)", name, H, Hk);
+  SA_REQUIRE(dk == kD && dv == kD, SA_EUNSUPPORTED, "%s: (dk,dv)=(%d,%d), only (128,128) is supported", name, dk, dv);
+  const int rows = req_idx ? n_req : B;
+  SA_REQUIRE(rows >= 0 && rows <= B, SA_EINVAL, "%s: n_req=%d outside [0,B=%d]", name, n_req, B);
+  if (rows == 0) return SA_OK;
+  SA_REQUIRE(q && k && v && alpha && beta && state_in && state_out && out, SA_EINVAL, "%s: null pointer", name);
+  SA_REQUIRE(sa::aligned(q, 16) && sa::aligned(k, 16) && sa::aligned(v, 16) && sa::aligned(state_in, 16) &&
+                 sa::aligned(state_out, 16) && sa::aligned(out, 16) && sa::aligned(alpha, 4) && sa::aligned(beta, 4) &&
+                 sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4),
+             SA_EINVAL, "%s: misaligned pointer", name);
+  SA_REQUIRE(static_cast<long long>(rows) * H <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many tiles", name);
+
+  ChunkParams p{static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+                alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale};
+  const unsigned lds_bytes = 2 * kStageB + 4 * kWaveB;
+  sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel, dim3(static_cast<unsigned>(rows * H)), dim3(256), lds_bytes,
+             static_cast<hipStream_t>(stream), p);
+  return sa::check_launch(name);
+}

@@ -1,0 +1,153 @@
+"""GPU parity of the chunk-parallel recurrent entry points against the step-by-step fp64 oracle (the printed
+recurrence), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixers as om
+from paper_2604_19877_amd import binding as sa
+from paper_2604_19877_amd import inputs as gen
+from gpu_util import OUT_TOL, STATE_TOL, Guarded, dev, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+FN = {False: (sa.gdn_chunk_steps, om.gdn_steps)}
+if hasattr(sa, "kda_chunk_steps"):
+    FN[True] = (sa.kda_chunk_steps, om.kda_steps)
+KINDS = sorted(FN)
+
+
+def run_chunked(kda, p, S0, B, T, H, Hk, scale, slot_idx=None, req_idx=None, n_slots=None):
+    d = {n: dev(a) for n, a in p.items()}
+    state = dev(S0.copy())
+    out = torch.full((B, T, H, 128), float("nan"), dtype=torch.float32, device="cuda")
+    FN[kda][0](d["q"], d["k"], d["v"], d["alpha"], d["beta"], state, state, out,
+               None if slot_idx is None else dev(slot_idx), None if req_idx is None else dev(req_idx),
+               0 if req_idx is None else len(req_idx), B, T, H, Hk, 128, 128, scale)
+    torch.cuda.synchronize()
+    return host(out), host(state)
+
+
+@pytest.mark.parametrize("kda", KINDS)
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 40, 64])
+@pytest.mark.parametrize("Hk", [4, 2])
+def test_chunked_call_equals_the_recurrence(kda, T, Hk):
+    """One call over T tokens (full chunks, a ragged tail, less than one chunk) against T oracle steps."""
+    B, H = 3, 4
+    p = gen.recurrent_inputs(4100 + T + 7 * Hk + kda, B, T, H, Hk, 128, 128, kda)
+    S0 = gen.recurrent_state(4200 + T, B * H, 128, 128).reshape(B, H, 128, 128)
+    scale = 128 ** -0.5
+    o, S = run_chunked(kda, p, S0, B, T, H, Hk, scale)
+    o_ref, S_ref = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, scale)
+    assert rel_err(o, o_ref) <= OUT_TOL
+    assert rel_err(S, S_ref) <= STATE_TOL
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_256_tokens_in_four_calls_state_tolerance(kda):
+    """The state tolerance is stated after 256 steps: 4 calls of 64 tokens, state carried in place."""
+    B, H, T, calls = 2, 4, 64, 4
+    p = gen.recurrent_inputs(4300 + kda, B, T * calls, H, H, 128, 128, kda)
+    S0 = gen.recurrent_state(4301, B * H, 128, 128).reshape(B, H, 128, 128)
+    scale = 128 ** -0.5
+    d = {n: dev(a) for n, a in p.items()}
+    state = dev(S0.copy())
+    outs = []
+    for c in range(calls):
+        sl = slice(c * T, (c + 1) * T)
+        out = torch.empty((B, T, H, 128), dtype=torch.float32, device="cuda")
+        FN[kda][0](d["q"][:, sl].contiguous(), d["k"][:, sl].contiguous(), d["v"][:, sl].contiguous(),
+                   d["alpha"][:, sl].contiguous(), d["beta"][:, sl].contiguous(), state, state, out, None, None, 0,
+                   B, T, H, H, 128, 128, scale)
+        outs.append(out)
+    torch.cuda.synchronize()
+    o = np.concatenate([host(x) for x in outs], axis=1)
+    o_ref, S_ref = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, scale)
+    assert rel_err(o, o_ref) <= OUT_TOL
+    assert rel_err(host(state), S_ref) <= STATE_TOL
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_slow_decay_and_strong_writes(kda):
+    """Gates near 1 (the state remembers the whole call) and beta near 1 with repeated keys: the triangular
+    system is then far from the identity."""
+    B, H, T = 2, 2, 48
+    p = gen.recurrent_inputs(4400 + kda, B, T, H, H, 128, 128, kda)
+    rng = np.random.default_rng(4401)
+    p["alpha"] = rng.uniform(0.97, 1.0, p["alpha"].shape).astype(np.float32)
+    p["beta"] = rng.uniform(0.9, 1.0, p["beta"].shape).astype(np.float32)
+    p["k"][:, 1::2] = p["k"][:, 0:-1:2]   # every second token repeats the key before it
+    S0 = gen.recurrent_state(4402, B * H, 128, 128).reshape(B, H, 128, 128)
+    o, S = run_chunked(kda, p, S0, B, T, H, H, 1.0)
+    o_ref, S_ref = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 1.0)
+    assert rel_err(o, o_ref) <= OUT_TOL
+    assert rel_err(S, S_ref) <= STATE_TOL
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_vanishing_gates_stay_finite(kda):
+    """Gates so small that their product over a chunk underflows fp32: the result must stay finite and right."""
+    B, H, T = 1, 2, 32
+    p = gen.recurrent_inputs(4500 + kda, B, T, H, H, 128, 128, kda)
+    p["alpha"] = np.full(p["alpha"].shape, 1e-4, dtype=np.float32)
+    S0 = gen.recurrent_state(4501, B * H, 128, 128).reshape(B, H, 128, 128)
+    o, S = run_chunked(kda, p, S0, B, T, H, H, 1.0)
+    o_ref, S_ref = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 1.0)
+    assert np.isfinite(o).all() and np.isfinite(S).all()
+    assert rel_err(o, o_ref) <= OUT_TOL
+    assert rel_err(S, S_ref) <= STATE_TOL
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_slots_request_list_and_untouched_rows(kda):
+    """State slots differ from batch rows, only listed rows run, everything else keeps its bytes."""
+    B, H, T, n_slots = 5, 2, 20, 7
+    p = gen.recurrent_inputs(4600 + kda, B, T, H, H, 128, 128, kda)
+    pool = gen.recurrent_state(4601, n_slots * H, 128, 128).reshape(n_slots, H, 128, 128)
+    slot_idx = np.array([6, 2, 0, 5, 3], dtype=np.int32)
+    req_idx = np.array([3, 0, 4], dtype=np.int32)
+    d = {n: dev(a) for n, a in p.items()}
+    gs = Guarded(pool.copy())
+    go = Guarded(np.full((B, T, H, 128), 7.0, dtype=np.float32))
+    FN[kda][0](d["q"], d["k"], d["v"], d["alpha"], d["beta"], gs.ptr(), gs.ptr(), go.ptr(), dev(slot_idx), dev(req_idx),
+               len(req_idx), B, T, H, H, 128, 128, 0.5)
+    torch.cuda.synchronize()
+    S, o = gs.read(), go.read()
+    assert gs.bands_intact() and go.bands_intact()
+    for b in range(B):
+        sl = slice(b, b + 1)
+        if b in req_idx:
+            o_ref, S_ref = FN[kda][1](p["q"][sl], p["k"][sl], p["v"][sl], p["alpha"][sl], p["beta"][sl],
+                                      pool[slot_idx[b]:slot_idx[b] + 1], 0.5)
+            assert rel_err(o[b], o_ref[0]) <= OUT_TOL
+            assert rel_err(S[slot_idx[b]], S_ref[0]) <= STATE_TOL
+        else:
+            assert (o[b] == 7.0).all()
+            assert np.array_equal(S[slot_idx[b]], pool[slot_idx[b]])
+    for s in set(range(n_slots)) - set(slot_idx.tolist()):
+        assert np.array_equal(S[s], pool[s])
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_chunked_matches_the_one_token_kernel_at_full_shape(kda):
+    """Batch 64 x 32 heads, 64 tokens: the chunked call and 64 single steps of the decode kernel agree
+    (both are checked against the oracle elsewhere; here every tile of the full launch is compared)."""
+    B, H, T = 64, 32, 64
+    p = gen.recurrent_inputs(4700 + kda, B, T, H, H, 128, 128, kda)
+    S0 = gen.recurrent_state(4701, B * H, 128, 128).reshape(B, H, 128, 128)
+    scale = 128 ** -0.5
+    o, S = run_chunked(kda, p, S0, B, T, H, H, scale)
+    d = {n: dev(a) for n, a in p.items()}
+    state = dev(S0.copy())
+    out = torch.empty((B, T, H, 128), dtype=torch.float32, device="cuda")
+    step = sa.kda_decode_step if kda else sa.gdn_decode_step
+    for c in range(T // 16):
+        sl = slice(16 * c, 16 * c + 16)
+        part = torch.empty((B, 16, H, 128), dtype=torch.float32, device="cuda")
+        step(d["q"][:, sl].contiguous(), d["k"][:, sl].contiguous(), d["v"][:, sl].contiguous(),
+             d["alpha"][:, sl].contiguous(), d["beta"][:, sl].contiguous(), state, state, part, None, None, 0,
+             B, 16, H, H, 128, 128, scale, 16)
+        out[:, sl] = part
+    torch.cuda.synchronize()
+    assert rel_err(o, host(out)) <= 1e-4
+    assert rel_err(S, host(state)) <= 1e-5
