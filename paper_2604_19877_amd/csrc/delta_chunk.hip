@@ -14,9 +14,8 @@
 // Precision.  States are fp32 and must stay within 1e-4 of the fp64 recurrence after hundreds of
 // steps, so nothing fp32 is rounded to one bf16: every fp32 operand of a matrix product is split into
 // several bf16 terms and the product is the sum of one bf16 MFMA per term with fp32 accumulation:
-// the corrections delta, which are added to the state, into three truncated terms (8 + 8 + 8
-// significant bits, exact); the state as an operand of K S_0 and Q S_0 into two rounded terms
-// (relative error 2^-18, unbiased; it reaches the state only through delta).  q, k arrive as bf16
+// two terms, each rounded to nearest (relative error 2^-18, unbiased), for the state as an operand
+// of K S_0 and Q S_0 and for the corrections delta added to it.  q, k arrive as bf16
 // and are used as they are.  The decay factors are applied in fp32 outside the products, as
 // 2^(difference of running sums of log2 alpha), which never exceeds 1 (no division, no overflow
 // for any alpha in (0,1]).
@@ -65,30 +64,8 @@ constexpr int kTokRowB = 272;    // bytes of one token row of K or Q in LDS (256
 constexpr int kChRowB = 40;      // bytes of one key-channel row (16 tokens, 32 + 8) of the channel-major K copy
 constexpr int kStageB = 2 * kC * kTokRowB + kD * kChRowB;  // one chunk's K, Q and transposed K
 constexpr int kMatRow = 20;      // floats per row of the per-wavefront 16x16 matrices (16 + 4)
-constexpr int kWaveB = (2 * kC * kMatRow + kC * 4) * 4;     // A (off-diagonal blocks), M, diagonal blocks of A
+constexpr int kWaveB = (2 * kC * kMatRow + kC * 4 + 64) * 4;  // A (off-diagonal blocks), M, diagonal blocks of A, dump slots
 
-// Top 16 bits of two floats as one packed bf16 pair (element 0 in the low half): truncation.
-__device__ __forceinline__ uint32_t pack_trunc(float lo, float hi) {
-  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
-}
-__device__ __forceinline__ float trunc_bf16(float x) { return __uint_as_float(__float_as_uint(x) & 0xffff0000u); }
-
-// Exact three-way split of 4 floats (one accumulator tile row group) into bf16 quadruples.
-struct Split4 {
-  u32x2 hi, mid, lo;
-};
-__device__ __forceinline__ Split4 split3(const f32x4& x) {
-  Split4 s;
-  float r[4], r2[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) r[e] = x[e] - trunc_bf16(x[e]);
-#pragma unroll
-  for (int e = 0; e < 4; ++e) r2[e] = r[e] - trunc_bf16(r[e]);
-  s.hi = u32x2{pack_trunc(x[0], x[1]), pack_trunc(x[2], x[3])};
-  s.mid = u32x2{pack_trunc(r[0], r[1]), pack_trunc(r[2], r[3])};
-  s.lo = u32x2{pack_trunc(r2[0], r2[1]), pack_trunc(r2[2], r2[3])};
-  return s;
-}
 // Two-term split with round-to-nearest in both terms: x = hi + lo up to 2^-18 |x|.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ uint32_t pack_rne(float lo, float hi) {
@@ -123,26 +100,34 @@ struct ChunkFetch {
   float alpha, beta;  // of token lane%16
 };
 
+// Tokens past the end of the call are read from the last valid token (always in bounds) and then
+// replaced by values that leave the state alone: k = q = v = 0, alpha = 1, beta = 0.
 __device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p, size_t row0, int t0, int h, int hk, int col,
                                             int g, int n) {
   const int tid = threadIdx.x;
   const int tok = tid >> 4, c8 = (tid & 15) * 8;
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-  f.kst = zero;
-  f.qst = zero;
-  if (t0 + tok < p.T) {
-    const size_t at = ((row0 + t0 + tok) * p.Hk + hk) * kD + c8;
-    f.kst = *reinterpret_cast<const u32x4*>(p.k + at);
-    f.qst = *reinterpret_cast<const u32x4*>(p.q + at);
+  const int last = p.T - 1;
+  {
+    const bool live = t0 + tok <= last;
+    const size_t at = ((row0 + min(t0 + tok, last)) * p.Hk + hk) * kD + c8;
+    const u32x4 kk = *reinterpret_cast<const u32x4*>(p.k + at), qq = *reinterpret_cast<const u32x4*>(p.q + at);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      f.kst[e] = live ? kk[e] : 0u;
+      f.qst[e] = live ? qq[e] : 0u;
+    }
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int t = t0 + 4 * g + j;
-    f.v[j] = t < p.T ? *reinterpret_cast<const uint32_t*>(p.v + ((row0 + t) * p.H + h) * kD + col) : 0u;
+    const uint32_t x = *reinterpret_cast<const uint32_t*>(p.v + ((row0 + min(t, last)) * p.H + h) * kD + col);
+    f.v[j] = t <= last ? x : 0u;
   }
   const int tn = t0 + n;
-  f.alpha = tn < p.T ? p.alpha[(row0 + tn) * p.H + h] : 1.f;
-  f.beta = tn < p.T ? p.beta[(row0 + tn) * p.H + h] : 0.f;
+  const size_t gi = (row0 + min(tn, last)) * p.H + h;
+  const float a = p.alpha[gi], bt = p.beta[gi];
+  f.alpha = tn <= last ? a : 1.f;
+  f.beta = tn <= last ? bt : 0.f;
 }
 
 __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
@@ -205,22 +190,27 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     // previous chunk's barrier since, so one barrier per chunk is enough.
     if (ch + 1 < n_chunks) fetch_chunk(nxt, p, row0, t0 + kC, h, hk, col, g, n);
 
-    // A operands of the 16x16x32 products: token n, key rows {32s+4g..+3, 32s+16+4g..+3}, the same
-    // rows as a pair of state tiles holds in this lane.
-    bf16x8 kf[4], qf[4];
+    // K S_0 and Q S_0 for this wavefront's 32 columns (rows = tokens 4g+j), and the Gram matrices
+    // (lane (n, g) gets k_t.k_n and q_t.k_n for t = 4g+j).  A operands of the 16x16x32 products: token n,
+    // key rows {32s+4g..+3, 32s+16+4g..+3}, the same rows as a pair of state tiles holds in this lane.
+    f32x4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
+    f32x4 u[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, w[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int off = n * kTokRowB + (32 * s + 4 * g) * 2;
-      kf[s] = join8(*reinterpret_cast<const u32x2*>(k_tok + off), *reinterpret_cast<const u32x2*>(k_tok + off + 32));
-      qf[s] = join8(*reinterpret_cast<const u32x2*>(q_tok + off), *reinterpret_cast<const u32x2*>(q_tok + off + 32));
-    }
-
-    // Gram matrices: lane (n, g) gets k_t.k_n and q_t.k_n for t = 4g+j.
-    f32x4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
+      const bf16x8 kf = join8(*reinterpret_cast<const u32x2*>(k_tok + off), *reinterpret_cast<const u32x2*>(k_tok + off + 32));
+      const bf16x8 qf = join8(*reinterpret_cast<const u32x2*>(q_tok + off), *reinterpret_cast<const u32x2*>(q_tok + off + 32));
+      kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, kf, kk, 0, 0, 0);
+      qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf, kf, qk, 0, 0, 0);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s], kf[s], kk, 0, 0, 0);
-      qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], kf[s], qk, 0, 0, 0);
+      for (int c = 0; c < 2; ++c) {
+        const Split4x2 lo_tile = split2(S[2 * s][c]), hi_tile = split2(S[2 * s + 1][c]);
+        const bf16x8 b_hi = join8(lo_tile.hi, hi_tile.hi), b_lo = join8(lo_tile.lo, hi_tile.lo);
+        u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, b_lo, u[c], 0, 0, 0);
+        w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf, b_lo, w[c], 0, 0, 0);
+        u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, b_hi, u[c], 0, 0, 0);
+        w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf, b_hi, w[c], 0, 0, 0);
+      }
     }
 
     // Decay factors from the running sum of log2(alpha): every g(t,i) = 2^(L_t - L_i) is at most 1, so no
@@ -230,7 +220,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
 #pragma unroll
     for (int d = 1; d < 16; d *= 2) {
       const float y = __shfl_up(log_sum, d, 16);
-      if (n >= d) log_sum += y;
+      log_sum += n >= d ? y : 0.f;
     }
     const float log_chunk = __shfl(log_sum, 15);
     float g_start[4], g_end[4], beta_t[4], ratio[4];
@@ -243,29 +233,16 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       beta_t[j] = __shfl(cur.beta, 4 * g + j);
     }
     const float g_chunk = exp2f(log_chunk);
+    const bool own_group = (n >> 2) == g;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int t = 4 * g + j;
       const float a = n < t ? beta_t[j] * ratio[j] * kk[j] : 0.f;
       a_off[t * kMatRow + n] = (n >> 2) < g ? a : 0.f;
-      if ((n >> 2) == g) a_dia[t * 4 + (n & 3)] = a;
+      a_dia[own_group ? t * 4 + (n & 3) : kC * 4 + lane] = a;  // other lanes write to a dump slot of their own
       m_low[t * kMatRow + n] = n <= t ? ratio[j] * qk[j] : 0.f;
     }
     wave_lds_sync();
-
-    // K S_0 and Q S_0 for this wavefront's 32 columns (rows = tokens 4g+j).
-    f32x4 u[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, w[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const Split4x2 lo_tile = split2(S[2 * s][c]), hi_tile = split2(S[2 * s + 1][c]);
-        const bf16x8 b_hi = join8(lo_tile.hi, hi_tile.hi), b_lo = join8(lo_tile.lo, hi_tile.lo);
-        u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s], b_lo, u[c], 0, 0, 0);
-        w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], b_lo, w[c], 0, 0, 0);
-        u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s], b_hi, u[c], 0, 0, 0);
-        w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[s], b_hi, w[c], 0, 0, 0);
-      }
 
     // Right-hand sides and the state's share of the read-out.
     f32x4 rhs[2], o[2];
@@ -283,12 +260,16 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     const f32x4 dia3 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 3) * 4);
 #pragma unroll
     for (int gp = 0; gp < 4; ++gp) {
-      if (g == gp) {
+      {
+        // The 4x4 solve inside group gp; the other groups run it with zero coefficients.
+        const bool now = g == gp;
+        const float c10 = now ? dia1[0] : 0.f, c20 = now ? dia2[0] : 0.f, c21 = now ? dia2[1] : 0.f;
+        const float c30 = now ? dia3[0] : 0.f, c31 = now ? dia3[1] : 0.f, c32 = now ? dia3[2] : 0.f;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-          rhs[c][1] -= dia1[0] * rhs[c][0];
-          rhs[c][2] -= dia2[0] * rhs[c][0] + dia2[1] * rhs[c][1];
-          rhs[c][3] -= dia3[0] * rhs[c][0] + dia3[1] * rhs[c][1] + dia3[2] * rhs[c][2];
+          rhs[c][1] = fmaf(-c10, rhs[c][0], rhs[c][1]);
+          rhs[c][2] = fmaf(-c21, rhs[c][1], fmaf(-c20, rhs[c][0], rhs[c][2]));
+          rhs[c][3] = fmaf(-c32, rhs[c][2], fmaf(-c31, rhs[c][1], fmaf(-c30, rhs[c][0], rhs[c][3])));
         }
       }
       if (gp == 3) break;  // nothing follows the last group
@@ -330,13 +311,13 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     }
 
     // S <- g(15,-1) S + K^T (g(15,t) delta_t): rows of the B operand are tokens.
-    Split4 ds[2];
+    Split4x2 ds[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       f32x4 x;
 #pragma unroll
       for (int j = 0; j < 4; ++j) x[j] = g_end[j] * rhs[c][j];
-      ds[c] = split3(x);
+      ds[c] = split2(x);
     }
 #pragma unroll
     for (int rt = 0; rt < 8; ++rt) {
@@ -347,7 +328,6 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[j] *= g_chunk;
         acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].lo), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].mid), acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].hi), acc, 0, 0, 0);
         S[rt][c] = acc;
       }
