@@ -73,15 +73,21 @@ sa_status kda_decode_step(const void* q, const void* k, const void* v, const flo
                           int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Many tokens per state pass: the same recurrence and read-out as gdn_decode_step, evaluated in its
- * chunk-parallel form (Appendix B: GDN runs "chunkwise" on a WY representation; Section 6: chunkwise
- * kernels serve prefill).  Tokens are processed 16 at a time as matrix products on the matrix cores with the
- * state held in registers across the whole call; results equal T chained single steps to fp32 rounding
- * (every fp32 operand of a product is split exactly into three bf16 terms).  Arguments as for
- * gdn_decode_step; any T >= 1; the state written is always the one after all T tokens (use gdn_decode_step
- * with n_commit for a roll-back).  Supported: (dk,dv) = (128,128).
+ * Many tokens per state pass: the same recurrences and read-out as gdn_decode_step / kda_decode_step,
+ * evaluated in their chunk-parallel form (Appendix B: GDN runs "chunkwise" on a WY representation, KDA on
+ * DPLR transitions; Section 6: chunkwise kernels serve prefill).  Tokens are processed 16 at a time as matrix
+ * products on the matrix cores with the state held in registers across the whole call.  Results equal T
+ * chained single steps up to rounding: every fp32 operand of a product enters as two bf16 terms (relative
+ * error 2^-18), which leaves outputs and states about 1e-5 from the fp64 recurrence.  Arguments as for the
+ * decode steps; any T >= 1; the state written is always the one after all T tokens (use the decode steps
+ * with n_commit for a roll-back).  Gates below 2^-100 act as 2^-100 in kda_chunk_steps and below the smallest
+ * normal fp32 number as that number in gdn_chunk_steps.  Supported: (dk,dv) = (128,128).
  */
 sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                          const float* state_in, float* state_out, float* out,
+                          const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                          int B, int T, int H, int Hk, int dk, int dv, float scale, void* stream);
+sa_status kda_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                           const float* state_in, float* state_out, float* out,
                           const int32_t* slot_idx, const int32_t* req_idx, int n_req,
                           int B, int T, int H, int Hk, int dk, int dv, float scale, void* stream);

@@ -55,6 +55,7 @@ _SIGNATURES = {
     "gdn_decode_step": (c_int, _RECURRENT_ARGS),
     "kda_decode_step": (c_int, _RECURRENT_ARGS),
     "gdn_chunk_steps": (c_int, _CHUNK_ARGS),
+    "kda_chunk_steps": (c_int, _CHUNK_ARGS),
     "gdn_block_decode": (c_int, _BLOCK_ARGS),
     "kda_block_decode": (c_int, _BLOCK_ARGS),
     "kv_append": (c_int, [c_void_p] * 4 + [c_int, c_void_p, c_int, c_void_p] + [c_int] * 5 + [c_void_p]),
@@ -157,6 +158,13 @@ def kda_decode_step(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, re
 def gdn_chunk_steps(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,
                     stream=None):
     _check(lib().gdn_chunk_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), _ptr(state_in), _ptr(state_out),
+                                 _ptr(out), _ptr(slot_idx), _ptr(req_idx), n_req, B, T, H, Hk, dk, dv, scale,
+                                 _stream(stream)))
+
+
+def kda_chunk_steps(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,
+                    stream=None):
+    _check(lib().kda_chunk_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), _ptr(state_in), _ptr(state_out),
                                  _ptr(out), _ptr(slot_idx), _ptr(req_idx), n_req, B, T, H, Hk, dk, dv, scale,
                                  _stream(stream)))
 

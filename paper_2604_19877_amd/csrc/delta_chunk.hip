@@ -93,6 +93,56 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Forward substitution (I + A) delta = rhs for this wavefront's 2 x 16 columns, rows 4 to a lane.
+// a_off holds A with the 4x4 diagonal blocks zeroed ([16][kMatRow]), a_dia those blocks ([16][4]).
+// Stage gp: the lanes of row group gp finish their 4 rows (the other groups run the same code with zero
+// coefficients), broadcast them, and the later groups subtract their block's share.
+__device__ __forceinline__ void solve_rows(f32x4 (&rhs)[2], const float* a_off, const float* a_dia, int n, int g) {
+  const f32x4 dia1 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 1) * 4);
+  const f32x4 dia2 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 2) * 4);
+  const f32x4 dia3 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 3) * 4);
+#pragma unroll
+  for (int gp = 0; gp < 4; ++gp) {
+    const bool now = g == gp;
+    const float c10 = now ? dia1[0] : 0.f, c20 = now ? dia2[0] : 0.f, c21 = now ? dia2[1] : 0.f;
+    const float c30 = now ? dia3[0] : 0.f, c31 = now ? dia3[1] : 0.f, c32 = now ? dia3[2] : 0.f;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      rhs[c][1] = fmaf(-c10, rhs[c][0], rhs[c][1]);
+      rhs[c][2] = fmaf(-c21, rhs[c][1], fmaf(-c20, rhs[c][0], rhs[c][2]));
+      rhs[c][3] = fmaf(-c32, rhs[c][2], fmaf(-c31, rhs[c][1], fmaf(-c30, rhs[c][0], rhs[c][3])));
+    }
+    if (gp == 3) break;  // nothing follows the last group
+    float d[2][4];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int jp = 0; jp < 4; ++jp) d[c][jp] = __shfl(rhs[c][jp], 16 * gp + n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(a_off + (4 * g + j) * kMatRow + 4 * gp);
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) rhs[c][j] = fmaf(-a[jp], d[c][jp], rhs[c][j]);
+    }
+  }
+}
+
+// Read-out: o += M delta on the matrix cores (m_low: [16][kMatRow], zero above the diagonal).  This product
+// only reaches the output (tolerance 2e-3), so two rounded terms per operand and the three leading cross
+// products are plenty.
+__device__ __forceinline__ void readout_rows(f32x4 (&o)[2], const f32x4 (&delta)[2], const float* m_low, int n, int g) {
+  const Split4x2 ms = split2(*reinterpret_cast<const f32x4*>(m_low + n * kMatRow + 4 * g));  // A operand: row n, columns 4g..
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const Split4x2 dl = split2(delta[c]);
+    o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.lo), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
+    o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.lo), o[c], 0, 0, 0);
+    o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
+  }
+}
+
 // What a thread fetches from global memory for one chunk.
 struct ChunkFetch {
   u32x4 kst, qst;     // staging: 8 channels of one token of K and of Q
@@ -254,52 +304,9 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       o[1][j] = g_start[j] * w[1][j];
     }
 
-    // Forward substitution by 4-row groups; rhs turns into delta in place.
-    const f32x4 dia1 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 1) * 4);
-    const f32x4 dia2 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 2) * 4);
-    const f32x4 dia3 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 3) * 4);
-#pragma unroll
-    for (int gp = 0; gp < 4; ++gp) {
-      {
-        // The 4x4 solve inside group gp; the other groups run it with zero coefficients.
-        const bool now = g == gp;
-        const float c10 = now ? dia1[0] : 0.f, c20 = now ? dia2[0] : 0.f, c21 = now ? dia2[1] : 0.f;
-        const float c30 = now ? dia3[0] : 0.f, c31 = now ? dia3[1] : 0.f, c32 = now ? dia3[2] : 0.f;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          rhs[c][1] = fmaf(-c10, rhs[c][0], rhs[c][1]);
-          rhs[c][2] = fmaf(-c21, rhs[c][1], fmaf(-c20, rhs[c][0], rhs[c][2]));
-          rhs[c][3] = fmaf(-c32, rhs[c][2], fmaf(-c31, rhs[c][1], fmaf(-c30, rhs[c][0], rhs[c][3])));
-        }
-      }
-      if (gp == 3) break;  // nothing follows the last group
-      float d[2][4];
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int jp = 0; jp < 4; ++jp) d[c][jp] = __shfl(rhs[c][jp], 16 * gp + n);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const f32x4 a = *reinterpret_cast<const f32x4*>(a_off + (4 * g + j) * kMatRow + 4 * gp);
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int jp = 0; jp < 4; ++jp) rhs[c][j] = fmaf(-a[jp], d[c][jp], rhs[c][j]);
-      }
-    }
-
-    // Read-out: o += M Delta on the matrix cores.  This product only reaches the output (tolerance
-    // 2e-3), so two rounded terms per operand and the three leading cross products are plenty.
-    {
-      const Split4x2 ms = split2(*reinterpret_cast<const f32x4*>(m_low + n * kMatRow + 4 * g));  // A operand: row n, columns 4g..
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const Split4x2 dl = split2(rhs[c]);
-        o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.lo), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
-        o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.lo), o[c], 0, 0, 0);
-        o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
-      }
-    }
+    // Forward substitution by 4-row groups (rhs turns into delta in place), then the read-out.
+    solve_rows(rhs, a_off, a_dia, n, g);
+    readout_rows(o, rhs, m_low, n, g);
 
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -345,13 +352,319 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// KDA: the gate is a vector over key channels, S_t = (I - beta_t k_t k_t^T) diag(alpha_t) S_{t-1} + beta_t k_t v_t^T.
+// With P_t = prod_{m<=t} alpha_m (per channel, from the chunk's first token) the same unrolling gives
+//     delta_t = beta_t (v_t - S_0^T (P_t k_t)) - sum_{i<t} beta_t ((P_t k_t).(k_i / P_i)) delta_i
+//     o_t     = scale ( S_0^T (P_t q_t) + sum_{i<=t} ((P_t q_t).(k_i / P_i)) delta_i )
+//     S_C     = diag(P_C) S_0 + sum_i (P_C / P_i) k_i delta_i^T
+// i.e. the GDN scheme with the decay folded into the operands: Khat = P k, Qhat = P q, Ktil = k / P and
+// Kend = (P_C / P) k are fp32 and enter the products as two rounded bf16 terms each.
+// k / P is the one place where a gate is divided by: P is kept >= 2^-100 by letting a pass cover only as
+// many tokens of the chunk as that allows (gates below 2^-100 act as 2^-100, so one token always fits);
+// the rest of the chunk follows in further passes over the same staged data.  With gates anywhere near
+// those of a trained model a pass is always the whole chunk.
+//
+// Staging per pass, two barriers: (1) 128 threads, one per key channel, run the product of gates down the
+// chunk, write P and 1/P tables and the number of tokens their channel allows; barrier; (2) every thread
+// scales the 8 channels of the one token whose raw k and q it fetched (coalesced 16-byte loads), splits
+// and stores them as MFMA operands, token-major for the A operands of the 16x16x32 products and
+// channel-major for K^T Delta; barrier; (3) each wavefront consumes them as in the GDN kernel.
+constexpr int kTabRow = kD;                                // floats per token row of the P and 1/P tables
+constexpr int kKdaTok = 6 * kC * kTokRowB;                 // Khat, Ktil, Qhat x (hi, lo), token-major
+constexpr int kKdaChn = 2 * kD * kChRowB;                  // Kend (hi, lo), channel-major
+constexpr int kKdaTab = 2 * kC * kTabRow * 4;              // P and 1/P
+constexpr int kKdaMisc = kD * 4 + 16;                      // P at the pass's last token per channel; token limits of 2 wavefronts
+constexpr int kKdaLds = kKdaTok + kKdaChn + kKdaTab + kKdaMisc + 4 * kWaveB;
+constexpr float kMinGate = 7.888609052e-31f;               // 2^-100
+
+struct KdaRaw {
+  u32x4 kst, qst;  // staging: 8 channels of one token of K and of Q
+};
+struct KdaLane {
+  uint32_t v[4];   // this lane's two value columns of tokens 4g .. 4g+3
+  float beta;      // of token lane%16
+};
+
+__device__ __forceinline__ void kda_fetch_raw(KdaRaw& f, const ChunkParams& p, size_t row0, int t0, int hk) {
+  const int tid = threadIdx.x;
+  const int tok = tid >> 4, c8 = (tid & 15) * 8;
+  const int last = p.T - 1;
+  const bool live = t0 + tok <= last;
+  const size_t at = ((row0 + min(t0 + tok, last)) * p.Hk + hk) * kD + c8;
+  const u32x4 kk = *reinterpret_cast<const u32x4*>(p.k + at), qq = *reinterpret_cast<const u32x4*>(p.q + at);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f.kst[e] = live ? kk[e] : 0u;
+    f.qst[e] = live ? qq[e] : 0u;
+  }
+}
+
+__device__ __forceinline__ void kda_fetch_lane(KdaLane& f, const ChunkParams& p, size_t row0, int t0, int h, int col, int g, int n) {
+  const int last = p.T - 1;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int t = t0 + 4 * g + j;
+    const uint32_t x = *reinterpret_cast<const uint32_t*>(p.v + ((row0 + min(t, last)) * p.H + h) * kD + col);
+    f.v[j] = t <= last ? x : 0u;
+  }
+  const int tn = t0 + n;
+  const float bt = p.beta[(row0 + min(tn, last)) * p.H + h];
+  f.beta = tn <= last ? bt : 0.f;
+}
+
+// The 16 gates of one key channel (thread tid < 128 owns channel tid); tokens past the end get 1.
+__device__ __forceinline__ void kda_fetch_gates(float (&al)[kC], const ChunkParams& p, size_t row0, int t0, int h, int chn) {
+  const int last = p.T - 1;
+#pragma unroll
+  for (int t = 0; t < kC; ++t) {
+    const float x = p.alpha[((row0 + min(t0 + t, last)) * p.H + h) * kD + chn];
+    al[t] = t0 + t <= last ? fmaxf(x, kMinGate) : 1.f;
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int r = blockIdx.x / p.H;
+  const int h = blockIdx.x - r * p.H;
+  const int b = p.req_idx ? p.req_idx[r] : r;
+  const int slot = p.slot_idx ? p.slot_idx[b] : b;
+  const int hk = h / (p.H / p.Hk);
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int n = lane & 15, g = lane >> 4;
+  const int col = wave * 32 + 2 * n;
+  const size_t row0 = static_cast<size_t>(b) * p.T;
+  const int chn = tid & (kD - 1);
+
+  // Token-major operand arrays in the order Khat hi, Khat lo, Ktil hi, Ktil lo, Qhat hi, Qhat lo.
+  unsigned char* const tok_arr = lds;
+  unsigned char* const kend_hi = lds + kKdaTok;
+  unsigned char* const kend_lo = kend_hi + kD * kChRowB;
+  float* const p_tab = reinterpret_cast<float*>(lds + kKdaTok + kKdaChn);   // [16][128] P_t per channel
+  float* const ip_tab = p_tab + kC * kTabRow;                               // [16][128] 1 / P_t
+  float* const p_end = ip_tab + kC * kTabRow;                               // [128] P at the last token of the pass
+  int* const limit = reinterpret_cast<int*>(p_end + kD);                    // [2] first token the channels of a wavefront refuse
+  float* const wave_mat = reinterpret_cast<float*>(lds + kKdaTok + kKdaChn + kKdaTab + kKdaMisc + wave * kWaveB);
+  float* const a_off = wave_mat;
+  float* const m_low = wave_mat + kC * kMatRow;
+  float* const a_dia = wave_mat + 2 * kC * kMatRow;
+
+  const size_t tile = (static_cast<size_t>(slot) * p.H + h) * (kD * kD);
+  const float* const sin = p.state_in + tile;
+  float* const sout = p.state_out + tile;
+  const uint32_t lane_off = static_cast<uint32_t>(4 * g * kD + col);
+
+  // raw and gates are needed only while a pass is being staged, so the next chunk's are fetched into
+  // the same registers as soon as the chunk's last pass has been staged.
+  KdaRaw raw;
+  KdaLane cur, nxt;
+  float gates[kC];
+  kda_fetch_raw(raw, p, row0, 0, hk);
+  kda_fetch_lane(cur, p, row0, 0, h, col, g, n);
+  if (tid < kD) kda_fetch_gates(gates, p, row0, 0, h, chn);
+  f32x4 S[8][2];
+#pragma unroll
+  for (int rt = 0; rt < 8; ++rt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x2 x = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sin + (lane_off + (16 * rt + j) * kD)));
+      S[rt][0][j] = x[0];
+      S[rt][1][j] = x[1];
+    }
+  __builtin_amdgcn_sched_barrier(0);
+
+  const int n_chunks = (p.T + kC - 1) / kC;
+  for (int ch = 0; ch < n_chunks; ++ch) {
+    const int t0 = ch * kC;
+    int first = 0;  // the pass covers tokens [first, stop) of the chunk
+    while (first < kC) {
+      // (1) Per channel: running product of gates from `first`, its reciprocal, and where it would drop below 2^-100.
+      if (tid < kD) {
+        float prod = 1.f;
+        int mine = kC;
+#pragma unroll
+        for (int t = 0; t < kC; ++t) {
+          const float next = prod * gates[t];
+          if (t >= first && mine == kC) {
+            if (next < kMinGate && t > first) {
+              mine = t;
+            } else {
+              prod = next;
+              p_tab[t * kTabRow + chn] = prod;
+              ip_tab[t * kTabRow + chn] = __builtin_amdgcn_rcpf(prod);
+            }
+          }
+        }
+#pragma unroll
+        for (int d = 1; d < 64; d *= 2) mine = min(mine, __shfl_xor(mine, d));
+        if (lane == 0) limit[wave] = mine;
+      }
+      __syncthreads();  // also: every wavefront has finished consuming the previous pass
+      const int stop = min(limit[0], limit[1]);
+
+      // (2) Operands of this pass from the raw token this thread fetched.
+      {
+        const int tok = tid >> 4, c8 = (tid & 15) * 8;
+        const bool live = tok >= first && tok < stop;
+        const f32x4 pa = *reinterpret_cast<const f32x4*>(p_tab + tok * kTabRow + c8),
+                    pb = *reinterpret_cast<const f32x4*>(p_tab + tok * kTabRow + c8 + 4);
+        const f32x4 ia = *reinterpret_cast<const f32x4*>(ip_tab + tok * kTabRow + c8),
+                    ib = *reinterpret_cast<const f32x4*>(ip_tab + tok * kTabRow + c8 + 4);
+        const f32x4 ea = *reinterpret_cast<const f32x4*>(p_tab + (stop - 1) * kTabRow + c8),
+                    eb = *reinterpret_cast<const f32x4*>(p_tab + (stop - 1) * kTabRow + c8 + 4);
+        if (tok == 0) {
+          *reinterpret_cast<f32x4*>(p_end + c8) = ea;
+          *reinterpret_cast<f32x4*>(p_end + c8 + 4) = eb;
+        }
+        float khat[8], ktil[8], qhat[8], kend[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t kw = raw.kst[e >> 1], qw = raw.qst[e >> 1];
+          const float kf = (e & 1) ? bf16_hi(kw) : bf16_lo(kw), qf = (e & 1) ? bf16_hi(qw) : bf16_lo(qw);
+          const float pt = e < 4 ? pa[e & 3] : pb[e & 3], it = e < 4 ? ia[e & 3] : ib[e & 3], pe = e < 4 ? ea[e & 3] : eb[e & 3];
+          khat[e] = live ? kf * pt : 0.f;
+          ktil[e] = live ? kf * it : 0.f;
+          qhat[e] = live ? qf * pt : 0.f;
+          kend[e] = live ? kf * (pe * it) : 0.f;
+        }
+        const float* const src[3] = {khat, ktil, qhat};
+#pragma unroll
+        for (int a = 0; a < 3; ++a) {
+          const Split4x2 x = split2(f32x4{src[a][0], src[a][1], src[a][2], src[a][3]}),
+                         y = split2(f32x4{src[a][4], src[a][5], src[a][6], src[a][7]});
+          unsigned char* const dst = tok_arr + (2 * a) * kC * kTokRowB + tok * kTokRowB + c8 * 2;
+          *reinterpret_cast<u32x4*>(dst) = u32x4{x.hi[0], x.hi[1], y.hi[0], y.hi[1]};
+          *reinterpret_cast<u32x4*>(dst + kC * kTokRowB) = u32x4{x.lo[0], x.lo[1], y.lo[0], y.lo[1]};
+        }
+        {
+          const Split4x2 x = split2(f32x4{kend[0], kend[1], kend[2], kend[3]}), y = split2(f32x4{kend[4], kend[5], kend[6], kend[7]});
+          const uint32_t hi[4] = {x.hi[0], x.hi[1], y.hi[0], y.hi[1]}, lo[4] = {x.lo[0], x.lo[1], y.lo[0], y.lo[1]};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int at = (c8 + e) * kChRowB + tok * 2;
+            *reinterpret_cast<uint16_t*>(kend_hi + at) = static_cast<uint16_t>((e & 1) ? (hi[e >> 1] >> 16) : (hi[e >> 1] & 0xffffu));
+            *reinterpret_cast<uint16_t*>(kend_lo + at) = static_cast<uint16_t>((e & 1) ? (lo[e >> 1] >> 16) : (lo[e >> 1] & 0xffffu));
+          }
+        }
+      }
+      __syncthreads();
+      const bool last_pass = stop == kC;
+      if (last_pass && ch + 1 < n_chunks) {
+        kda_fetch_raw(raw, p, row0, t0 + kC, hk);
+        kda_fetch_lane(nxt, p, row0, t0 + kC, h, col, g, n);
+        if (tid < kD) kda_fetch_gates(gates, p, row0, t0 + kC, h, chn);
+      }
+
+      // (3) Gram matrices and Khat S_0, Qhat S_0 (three leading cross products of the two-term operands).
+      f32x4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
+      f32x4 u[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, w[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int off = n * kTokRowB + (32 * s + 4 * g) * 2;
+        bf16x8 f[6];
+#pragma unroll
+        for (int a = 0; a < 6; ++a) {
+          const unsigned char* const src = tok_arr + a * kC * kTokRowB + off;
+          f[a] = join8(*reinterpret_cast<const u32x2*>(src), *reinterpret_cast<const u32x2*>(src + 32));
+        }
+        // f: Khat hi, Khat lo, Ktil hi, Ktil lo, Qhat hi, Qhat lo
+        kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[1], f[2], kk, 0, 0, 0);
+        kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0], f[3], kk, 0, 0, 0);
+        kk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0], f[2], kk, 0, 0, 0);
+        qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[5], f[2], qk, 0, 0, 0);
+        qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[4], f[3], qk, 0, 0, 0);
+        qk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[4], f[2], qk, 0, 0, 0);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const Split4x2 lo_tile = split2(S[2 * s][c]), hi_tile = split2(S[2 * s + 1][c]);
+          const bf16x8 b_hi = join8(lo_tile.hi, hi_tile.hi), b_lo = join8(lo_tile.lo, hi_tile.lo);
+          u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[1], b_hi, u[c], 0, 0, 0);
+          w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[5], b_hi, w[c], 0, 0, 0);
+          u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0], b_lo, u[c], 0, 0, 0);
+          w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[4], b_lo, w[c], 0, 0, 0);
+          u[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0], b_hi, u[c], 0, 0, 0);
+          w[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[4], b_hi, w[c], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keeps the next slice's 6 fragments and splits out of this one's registers
+      }
+
+      float beta_t[4];
+      const bool own_group = (n >> 2) == g;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int t = 4 * g + j;
+        const float bt = __shfl(cur.beta, t);
+        beta_t[j] = (t >= first && t < stop) ? bt : 0.f;
+        const float a = n < t ? beta_t[j] * kk[j] : 0.f;
+        a_off[t * kMatRow + n] = (n >> 2) < g ? a : 0.f;
+        a_dia[own_group ? t * 4 + (n & 3) : kC * 4 + lane] = a;
+        m_low[t * kMatRow + n] = n <= t ? qk[j] : 0.f;
+      }
+      wave_lds_sync();
+
+      f32x4 rhs[2], o[2];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        rhs[0][j] = beta_t[j] * (bf16_lo(cur.v[j]) - u[0][j]);
+        rhs[1][j] = beta_t[j] * (bf16_hi(cur.v[j]) - u[1][j]);
+      }
+      o[0] = w[0];
+      o[1] = w[1];
+      solve_rows(rhs, a_off, a_dia, n, g);
+      readout_rows(o, rhs, m_low, n, g);
+
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int t = 4 * g + j;
+        if (t >= first && t < stop && t0 + t < p.T) {
+          const f32x2 y = {p.scale * o[0][j], p.scale * o[1][j]};
+          *reinterpret_cast<f32x2*>(p.out + ((row0 + t0 + t) * p.H + h) * kD + col) = y;
+        }
+      }
+
+      // S <- diag(P_end) S + Kend^T Delta.
+      Split4x2 ds[2] = {split2(rhs[0]), split2(rhs[1])};
+#pragma unroll
+      for (int rt = 0; rt < 8; ++rt) {
+        const int at = (16 * rt + n) * kChRowB + 8 * g;
+        const s16x4 e_hi = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(kend_hi + at));
+        const s16x4 e_lo = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(kend_lo + at));
+        const f32x4 row_scale = *reinterpret_cast<const f32x4*>(p_end + 16 * rt + 4 * g);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          f32x4 acc = S[rt][c];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[j] *= row_scale[j];
+          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(e_lo, __builtin_bit_cast(s16x4, ds[c].hi), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(e_hi, __builtin_bit_cast(s16x4, ds[c].lo), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(e_hi, __builtin_bit_cast(s16x4, ds[c].hi), acc, 0, 0, 0);
+          S[rt][c] = acc;
+        }
+      }
+      first = stop;
+    }
+    cur = nxt;
+  }
+
+#pragma unroll
+  for (int rt = 0; rt < 8; ++rt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x2 x = {S[rt][0][j], S[rt][1][j]};
+      __builtin_nontemporal_store(x, reinterpret_cast<f32x2*>(sout + (lane_off + (16 * rt + j) * kD)));
+    }
+}
+
 }  // namespace
 
-extern "C" sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
-                                     const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
-                                     const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
-                                     float scale, void* stream) {
-  const char* name = "gdn_chunk_steps";
+namespace {
+
+template <bool KDA>
+sa_status chunk_launch(const char* name, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                       const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
+                       int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, void* stream) {
   SA_REQUIRE(B >= 0 && T >= 1, SA_EINVAL, "%s: need B >= 0 and T >= 1 (B=%d, T=%d)", name, B, T);
   SA_REQUIRE(H >= 1 && Hk >= 1 && H % Hk == 0, SA_EINVAL, "%s: H must be a positive multiple of Hk (H=%d, Hk=%d)", name, H, Hk);
   SA_REQUIRE(dk == kD && dv == kD, SA_EUNSUPPORTED, "%s: (dk,dv)=(%d,%d), only (128,128) is supported", name, dk, dv);
@@ -367,8 +680,37 @@ extern "C" sa_status gdn_chunk_steps(const void* q, const void* k, const void* v
 
   ChunkParams p{static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                 alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale};
-  const unsigned lds_bytes = 2 * kStageB + 4 * kWaveB;
-  sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel, dim3(static_cast<unsigned>(rows * H)), dim3(256), lds_bytes,
-             static_cast<hipStream_t>(stream), p);
+  const dim3 grid(static_cast<unsigned>(rows * H));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (KDA) {
+    static bool lds_raised = false;  // more than the default 64 KiB of dynamic LDS must be asked for once
+    if (!lds_raised) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kda_chunk_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kKdaLds);
+      if (e != hipSuccess) return sa::fail(SA_EHIP, "%s: %s", name, hipGetErrorString(e));
+      lds_raised = true;
+    }
+    sa::launch(SA_K_KDA_CHUNK, kda_chunk_kernel, grid, dim3(256), kKdaLds, s, p);
+  } else {
+    sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel, grid, dim3(256), 2 * kStageB + 4 * kWaveB, s, p);
+  }
   return sa::check_launch(name);
+}
+
+}  // namespace
+
+extern "C" sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                                     const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                                     const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
+                                     float scale, void* stream) {
+  return chunk_launch<false>("gdn_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
+                             Hk, dk, dv, scale, stream);
+}
+
+extern "C" sa_status kda_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                                     const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                                     const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
+                                     float scale, void* stream) {
+  return chunk_launch<true>("kda_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
+                            Hk, dk, dv, scale, stream);
 }

@@ -98,6 +98,24 @@ def test_vanishing_gates_stay_finite(kda):
     assert rel_err(S, S_ref) <= STATE_TOL
 
 
+def test_kda_few_channels_with_tiny_gates_split_the_chunk():
+    """A handful of key channels decay by 1e-9 per token while the rest follow the recipe: the product of
+    gates over a chunk leaves the range in which it can be divided by, so chunks run in several passes."""
+    if True not in FN:
+        pytest.skip("no chunked KDA entry point")
+    B, H, T = 2, 2, 40
+    p = gen.recurrent_inputs(4550, B, T, H, H, 128, 128, True)
+    rng = np.random.default_rng(4551)
+    tiny = rng.random(p["alpha"].shape) < 0.03
+    p["alpha"] = np.where(tiny, np.float32(1e-9), p["alpha"]).astype(np.float32)
+    S0 = gen.recurrent_state(4552, B * H, 128, 128).reshape(B, H, 128, 128)
+    o, S = run_chunked(True, p, S0, B, T, H, H, 1.0)
+    o_ref, S_ref = om.kda_steps(p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 1.0)
+    assert np.isfinite(o).all() and np.isfinite(S).all()
+    assert rel_err(o, o_ref) <= OUT_TOL
+    assert rel_err(S, S_ref) <= STATE_TOL
+
+
 @pytest.mark.parametrize("kda", KINDS)
 def test_slots_request_list_and_untouched_rows(kda):
     """State slots differ from batch rows, only listed rows run, everything else keeps its bytes."""
