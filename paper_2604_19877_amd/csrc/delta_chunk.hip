@@ -184,8 +184,9 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int r = blockIdx.x / p.H;
   const int h = blockIdx.x - r * p.H;
-  const int b = p.req_idx ? p.req_idx[r] : r;
-  const int slot = p.slot_idx ? p.slot_idx[b] : b;
+  // Both indices are the same for the whole workgroup; saying so keeps every base address in scalar registers.
+  const int b = __builtin_amdgcn_readfirstlane(p.req_idx ? p.req_idx[r] : r);
+  const int slot = __builtin_amdgcn_readfirstlane(p.slot_idx ? p.slot_idx[b] : b);
   const int hk = h / (p.H / p.Hk);
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -387,49 +388,51 @@ struct KdaLane {
   float beta;      // of token lane%16
 };
 
+// All fetches address a uniform per-chunk base with a 32-bit lane offset (a chunk spans < 4 GiB).  Tokens
+// past the end of the call are read from the last valid token, which keeps every address in bounds; no
+// pass ever covers them, so what they hold does not matter.
+// Offsets are formed in bytes in 32 bits so that a load is "scalar base + vector offset".
+template <typename V>
+__device__ __forceinline__ V load_at(const void* base, uint32_t byte_off) {
+  return *reinterpret_cast<const V*>(static_cast<const unsigned char*>(base) + byte_off);
+}
+
 __device__ __forceinline__ void kda_fetch_raw(KdaRaw& f, const ChunkParams& p, size_t row0, int t0, int hk) {
   const int tid = threadIdx.x;
   const int tok = tid >> 4, c8 = (tid & 15) * 8;
-  const int last = p.T - 1;
-  const bool live = t0 + tok <= last;
-  const size_t at = ((row0 + min(t0 + tok, last)) * p.Hk + hk) * kD + c8;
-  const u32x4 kk = *reinterpret_cast<const u32x4*>(p.k + at), qq = *reinterpret_cast<const u32x4*>(p.q + at);
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    f.kst[e] = live ? kk[e] : 0u;
-    f.qst[e] = live ? qq[e] : 0u;
-  }
+  const int lim = p.T - 1 - t0;  // last valid token of the chunk
+  const size_t base = ((row0 + t0) * p.Hk + hk) * kD;
+  const uint32_t off = (static_cast<uint32_t>(min(tok, lim)) * static_cast<uint32_t>(p.Hk * kD) + c8) * 2u;
+  f.kst = load_at<u32x4>(p.k + base, off);
+  f.qst = load_at<u32x4>(p.q + base, off);
 }
 
 __device__ __forceinline__ void kda_fetch_lane(KdaLane& f, const ChunkParams& p, size_t row0, int t0, int h, int col, int g, int n) {
-  const int last = p.T - 1;
+  const int lim = p.T - 1 - t0;
+  const size_t base = ((row0 + t0) * p.H + h);
+  const uint32_t stride = static_cast<uint32_t>(p.H * kD);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int t = t0 + 4 * g + j;
-    const uint32_t x = *reinterpret_cast<const uint32_t*>(p.v + ((row0 + min(t, last)) * p.H + h) * kD + col);
-    f.v[j] = t <= last ? x : 0u;
-  }
-  const int tn = t0 + n;
-  const float bt = p.beta[(row0 + min(tn, last)) * p.H + h];
-  f.beta = tn <= last ? bt : 0.f;
+  for (int j = 0; j < 4; ++j)
+    f.v[j] = load_at<uint32_t>(p.v + base * kD, (static_cast<uint32_t>(min(4 * g + j, lim)) * stride + col) * 2u);
+  f.beta = load_at<float>(p.beta + base, static_cast<uint32_t>(min(n, lim)) * static_cast<uint32_t>(p.H) * 4u);
 }
 
-// The 16 gates of one key channel (thread tid < 128 owns channel tid); tokens past the end get 1.
+// The 16 gates of one key channel (thread tid < 128 owns channel tid).
 __device__ __forceinline__ void kda_fetch_gates(float (&al)[kC], const ChunkParams& p, size_t row0, int t0, int h, int chn) {
-  const int last = p.T - 1;
+  const int lim = p.T - 1 - t0;
+  const float* const base = p.alpha + ((row0 + t0) * p.H + h) * kD;
+  const uint32_t stride = static_cast<uint32_t>(p.H * kD);
 #pragma unroll
-  for (int t = 0; t < kC; ++t) {
-    const float x = p.alpha[((row0 + min(t0 + t, last)) * p.H + h) * kD + chn];
-    al[t] = t0 + t <= last ? fmaxf(x, kMinGate) : 1.f;
-  }
+  for (int t = 0; t < kC; ++t) al[t] = fmaxf(load_at<float>(base, (static_cast<uint32_t>(min(t, lim)) * stride + chn) * 4u), kMinGate);
 }
 
 __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int r = blockIdx.x / p.H;
   const int h = blockIdx.x - r * p.H;
-  const int b = p.req_idx ? p.req_idx[r] : r;
-  const int slot = p.slot_idx ? p.slot_idx[b] : b;
+  // Both indices are the same for the whole workgroup; saying so keeps every base address in scalar registers.
+  const int b = __builtin_amdgcn_readfirstlane(p.req_idx ? p.req_idx[r] : r);
+  const int slot = __builtin_amdgcn_readfirstlane(p.slot_idx ? p.slot_idx[b] : b);
   const int hk = h / (p.H / p.Hk);
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -478,31 +481,27 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
   const int n_chunks = (p.T + kC - 1) / kC;
   for (int ch = 0; ch < n_chunks; ++ch) {
     const int t0 = ch * kC;
+    const int n_tok = min(kC, p.T - t0);
     int first = 0;  // the pass covers tokens [first, stop) of the chunk
-    while (first < kC) {
+    while (first < n_tok) {
       // (1) Per channel: running product of gates from `first`, its reciprocal, and where it would drop below 2^-100.
       if (tid < kD) {
+        // The product keeps running past the token where it leaves the range; those entries are never used.
         float prod = 1.f;
-        int mine = kC;
+        int mine = n_tok;
 #pragma unroll
         for (int t = 0; t < kC; ++t) {
-          const float next = prod * gates[t];
-          if (t >= first && mine == kC) {
-            if (next < kMinGate && t > first) {
-              mine = t;
-            } else {
-              prod = next;
-              p_tab[t * kTabRow + chn] = prod;
-              ip_tab[t * kTabRow + chn] = __builtin_amdgcn_rcpf(prod);
-            }
-          }
+          prod *= t >= first ? gates[t] : 1.f;
+          mine = (prod < kMinGate && t > first) ? min(mine, t) : mine;
+          p_tab[t * kTabRow + chn] = prod;
+          ip_tab[t * kTabRow + chn] = __builtin_amdgcn_rcpf(prod);
         }
 #pragma unroll
         for (int d = 1; d < 64; d *= 2) mine = min(mine, __shfl_xor(mine, d));
         if (lane == 0) limit[wave] = mine;
       }
       __syncthreads();  // also: every wavefront has finished consuming the previous pass
-      const int stop = min(limit[0], limit[1]);
+      const int stop = __builtin_amdgcn_readfirstlane(min(limit[0], limit[1]));  // the same for all lanes
 
       // (2) Operands of this pass from the raw token this thread fetched.
       {
@@ -550,13 +549,6 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
         }
       }
       __syncthreads();
-      const bool last_pass = stop == kC;
-      if (last_pass && ch + 1 < n_chunks) {
-        kda_fetch_raw(raw, p, row0, t0 + kC, hk);
-        kda_fetch_lane(nxt, p, row0, t0 + kC, h, col, g, n);
-        if (tid < kD) kda_fetch_gates(gates, p, row0, t0 + kC, h, chn);
-      }
-
       // (3) Gram matrices and Khat S_0, Qhat S_0 (three leading cross products of the two-term operands).
       f32x4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
       f32x4 u[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, w[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
@@ -604,6 +596,19 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
       }
       wave_lds_sync();
 
+      // The next chunk's inputs are requested here, after the register-hungry products above.
+      __builtin_amdgcn_sched_barrier(0);
+      if (stop == n_tok && ch + 1 < n_chunks) {
+        // An opaque copy of the next chunk's first token: otherwise the addresses below are formed at the top
+        // of the chunk as 64-bit vector pointers, one per load, and live (or spill) through all of it.
+        int t_next = t0 + kC;
+        asm volatile("" : "+s"(t_next));
+        kda_fetch_raw(raw, p, row0, t_next, hk);
+        kda_fetch_lane(nxt, p, row0, t_next, h, col, g, n);
+        if (tid < kD) kda_fetch_gates(gates, p, row0, t_next, h, chn);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+
       f32x4 rhs[2], o[2];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -618,7 +623,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int t = 4 * g + j;
-        if (t >= first && t < stop && t0 + t < p.T) {
+        if (t >= first && t < stop) {
           const f32x2 y = {p.scale * o[0][j], p.scale * o[1][j]};
           *reinterpret_cast<f32x2*>(p.out + ((row0 + t0 + t) * p.H + h) * kD + col) = y;
         }
