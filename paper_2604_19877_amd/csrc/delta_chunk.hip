@@ -143,6 +143,12 @@ __device__ __forceinline__ void readout_rows(f32x4 (&o)[2], const f32x4 (&delta)
   }
 }
 
+// Offsets are formed in bytes in 32 bits so that a load is "scalar base + vector offset".
+template <typename V>
+__device__ __forceinline__ V load_at(const void* base, uint32_t byte_off) {
+  return *reinterpret_cast<const V*>(static_cast<const unsigned char*>(base) + byte_off);
+}
+
 // What a thread fetches from global memory for one chunk.
 struct ChunkFetch {
   u32x4 kst, qst;     // staging: 8 channels of one token of K and of Q
@@ -151,33 +157,36 @@ struct ChunkFetch {
 };
 
 // Tokens past the end of the call are read from the last valid token (always in bounds) and then
-// replaced by values that leave the state alone: k = q = v = 0, alpha = 1, beta = 0.
+// replaced by values that leave the state alone: k = q = v = 0, alpha = 1, beta = 0.  All addresses are
+// a per-chunk scalar base plus a 32-bit lane offset (a chunk spans < 4 GiB).
 __device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p, size_t row0, int t0, int h, int hk, int col,
                                             int g, int n) {
   const int tid = threadIdx.x;
   const int tok = tid >> 4, c8 = (tid & 15) * 8;
-  const int last = p.T - 1;
+  const int lim = p.T - 1 - t0;  // last valid token of the chunk
   {
-    const bool live = t0 + tok <= last;
-    const size_t at = ((row0 + min(t0 + tok, last)) * p.Hk + hk) * kD + c8;
-    const u32x4 kk = *reinterpret_cast<const u32x4*>(p.k + at), qq = *reinterpret_cast<const u32x4*>(p.q + at);
+    const size_t base = ((row0 + t0) * p.Hk + hk) * kD;
+    const uint32_t off = (static_cast<uint32_t>(min(tok, lim)) * static_cast<uint32_t>(p.Hk * kD) + c8) * 2u;
+    const u32x4 kk = load_at<u32x4>(p.k + base, off), qq = load_at<u32x4>(p.q + base, off);
+    const bool live = tok <= lim;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       f.kst[e] = live ? kk[e] : 0u;
       f.qst[e] = live ? qq[e] : 0u;
     }
   }
+  const size_t base = (row0 + t0) * p.H + h;
+  const uint32_t stride = static_cast<uint32_t>(p.H * kD);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int t = t0 + 4 * g + j;
-    const uint32_t x = *reinterpret_cast<const uint32_t*>(p.v + ((row0 + min(t, last)) * p.H + h) * kD + col);
-    f.v[j] = t <= last ? x : 0u;
+    const int t = 4 * g + j;
+    const uint32_t x = load_at<uint32_t>(p.v + base * kD, (static_cast<uint32_t>(min(t, lim)) * stride + col) * 2u);
+    f.v[j] = t <= lim ? x : 0u;
   }
-  const int tn = t0 + n;
-  const size_t gi = (row0 + min(tn, last)) * p.H + h;
-  const float a = p.alpha[gi], bt = p.beta[gi];
-  f.alpha = tn <= last ? a : 1.f;
-  f.beta = tn <= last ? bt : 0.f;
+  const uint32_t gi = static_cast<uint32_t>(min(n, lim)) * static_cast<uint32_t>(p.H) * 4u;
+  const float a = load_at<float>(p.alpha + base, gi), bt = load_at<float>(p.beta + base, gi);
+  f.alpha = n <= lim ? a : 1.f;
+  f.beta = n <= lim ? bt : 0.f;
 }
 
 __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
@@ -239,7 +248,12 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     __syncthreads();
     // The buffer written above was last read two chunks ago, and every wavefront has passed the
     // previous chunk's barrier since, so one barrier per chunk is enough.
-    if (ch + 1 < n_chunks) fetch_chunk(nxt, p, row0, t0 + kC, h, hk, col, g, n);
+    if (ch + 1 < n_chunks) {
+      // An opaque copy of the next chunk's first token keeps the address arithmetic here, in scalar registers.
+      int t_next = t0 + kC;
+      asm volatile("" : "+s"(t_next));
+      fetch_chunk(nxt, p, row0, t_next, h, hk, col, g, n);
+    }
 
     // K S_0 and Q S_0 for this wavefront's 32 columns (rows = tokens 4g+j), and the Gram matrices
     // (lane (n, g) gets k_t.k_n and q_t.k_n for t = 4g+j).  A operands of the 16x16x32 products: token n,
@@ -391,12 +405,6 @@ struct KdaLane {
 // All fetches address a uniform per-chunk base with a 32-bit lane offset (a chunk spans < 4 GiB).  Tokens
 // past the end of the call are read from the last valid token, which keeps every address in bounds; no
 // pass ever covers them, so what they hold does not matter.
-// Offsets are formed in bytes in 32 bits so that a load is "scalar base + vector offset".
-template <typename V>
-__device__ __forceinline__ V load_at(const void* base, uint32_t byte_off) {
-  return *reinterpret_cast<const V*>(static_cast<const unsigned char*>(base) + byte_off);
-}
-
 __device__ __forceinline__ void kda_fetch_raw(KdaRaw& f, const ChunkParams& p, size_t row0, int t0, int hk) {
   const int tid = threadIdx.x;
   const int tok = tid >> 4, c8 = (tid & 15) * 8;
