@@ -46,6 +46,8 @@ def parse_args():
     ap.add_argument("--cost-table", action="store_true",
                     help="only fit the per-mixer cost model 1/throughput = sum_m c_m n_m over 14 allocations of a 48-layer "
                          "stack (batch 32, 16384-token contexts) and print it")
+    ap.add_argument("--prefill", type=int, default=0, metavar="T",
+                    help="only run the chunk-parallel recurrent kernels over T tokens per sequence (batch 64) and print their times")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the plain 1 GiB copy kernel 3 times after the timed region (counter calibration)")
     return ap.parse_args()
@@ -68,6 +70,12 @@ def main():
     stream = torch.cuda.current_stream()
     if args.cost_table:
         print(json.dumps(cost_table(np, torch, gen, stream)))
+        return
+    if args.prefill > 0:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(1234)
+        print(json.dumps({"workload": "chunk-parallel recurrent prefill, 64 sequences x 32 heads x %d tokens" % args.prefill,
+                          **chunk_cases(torch, sa, args.prefill, DK ** -0.5, stream, g)}))
         return
 
     def dev(a):
@@ -277,7 +285,8 @@ def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_
 def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages, lens_swa, lens_swa_h, rec_scale, attn_scale,
                 stream, g, reps=12):
     """Batch 256 for the recurrent mixers (bandwidth saturation), the recurrent steps launched back to back
-    (no read-only kernel in between to hide their write-back), and full attention at ragged lengths."""
+    (no read-only kernel in between to hide their write-back), the whole-block step, the chunk-parallel kernels
+    at 16 to 512 tokens per sequence, and full attention at ragged lengths."""
     res = {}
     for nb, sets in ((256, 4), (64, 8)):
         for name, kda, fn, kid in (("gdn", False, sa.gdn_decode_step, sa.SA_K_GDN), ("kda", True, sa.kda_decode_step, sa.SA_K_KDA)):
@@ -327,6 +336,9 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
             "avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1), "alg_bytes": nbytes,
             "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del states
+    # many tokens per state pass (prefill-like): the chunk-parallel kernels at 16, 64 and 512 tokens per sequence
+    for T in (16, 64, 512):
+        res.update(chunk_cases(torch, sa, T, rec_scale, stream, g))
     q = dev(gen.attention_inputs(1820, B, 1, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"])
     ws_bytes = sa.attn_decode_workspace_bytes(B, 1, HQ, HKV, D, CTX, 0)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
@@ -343,6 +355,36 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
     nbytes = int(lens_swa_h.astype(np.int64).sum()) * 2 * HKV * D * 2
     res["fa_ragged_U8192_32768"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1),
                                     "alg_bytes": nbytes, "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    return res
+
+
+def chunk_cases(torch, sa, T, rec_scale, stream, g, reps=6):
+    """gdn_chunk_steps / kda_chunk_steps over T tokens for each of 64 sequences x 32 heads; inputs drawn on the
+    device with the recipe's distributions, states rotating over 4 sets."""
+    res = {}
+    nrm = lambda x: (x / x.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    xq = nrm(torch.empty((B, T, H, DK), device="cuda").normal_(generator=g).bfloat16().float())
+    xk = nrm(torch.empty((B, T, H, DK), device="cuda").normal_(generator=g).bfloat16().float())
+    xv = torch.empty((B, T, H, DV), device="cuda").normal_(generator=g).bfloat16()
+    beta = torch.sigmoid(torch.empty((B, T, H), device="cuda").normal_(generator=g))
+    states = torch.empty((4, B * H, DK, DV), dtype=torch.float32, device="cuda")
+    states.normal_(0.0, 0.02, generator=g)
+    out = torch.empty((B, T, H, DV), dtype=torch.float32, device="cuda")
+    for name, kda, fn, kid in (("gdn", False, sa.gdn_chunk_steps, sa.SA_K_GDN_CHUNK),
+                               ("kda", True, sa.kda_chunk_steps, sa.SA_K_KDA_CHUNK)):
+        alpha = torch.exp(-torch.nn.functional.softplus(
+            torch.empty((B, T, H, DK) if kda else (B, T, H), device="cuda").normal_(generator=g) + 2.0))
+        sa.sa_prof_enable(True)
+        for i in range(reps):
+            s = states[i % 4]
+            fn(xq, xk, xv, alpha, beta, s, s, out, None, None, 0, B, T, H, H, DK, DV, rec_scale, stream)
+        torch.cuda.synchronize()
+        sa.sa_prof_enable(False)
+        _, _, ms = sa.sa_prof_read(kid, reps)
+        avg = sum(ms[2:]) / (len(ms) - 2)
+        res["%s_chunk_T%d" % (name, T)] = {"avg_us": round(avg * 1e3, 2), "us_per_token": round(avg * 1e3 / T, 3),
+                                           "tokens_per_s": round(B * T / (avg * 1e-3), 1)}
+        del alpha
     return res
 
 
