@@ -53,6 +53,24 @@ def test_recurrent_argument_errors(fn):
     _recurrent_call(fn, req_idx=16, n_req=0)       # empty request list
 
 
+@pytest.mark.parametrize("fn", [sa.gdn_chunk_steps, sa.kda_chunk_steps])
+def test_chunked_recurrent_argument_errors(fn):
+    def call(**over):
+        a = dict(q=16, k=16, v=16, alpha=16, beta=16, state_in=16, state_out=16, out=16, slot_idx=None, req_idx=None,
+                 n_req=0, B=2, T=40, H=4, Hk=4, dk=128, dv=128, scale=1.0, stream=0)
+        a.update(over)
+        fn(**a)
+    with pytest.raises(sa.SaError) as e:
+        call(dk=64, dv=64)                # the one-token kernels take this shape, the chunked ones do not
+    assert e.value.status == sa.SA_EUNSUPPORTED and "64" in str(e.value)
+    for bad in (dict(T=0), dict(Hk=3), dict(v=None), dict(out=4), dict(req_idx=16, n_req=3), dict(B=-1)):
+        with pytest.raises(sa.SaError) as e:
+            call(**bad)
+        assert e.value.status == sa.SA_EINVAL, bad
+    call(B=0)
+    call(req_idx=16, n_req=0)
+
+
 def _attn_call(**over):
     a = dict(q=16, kpool=16, vpool=16, n_pages=4, page_table=16, max_pages=4, seq_lens=16, req_idx=None, n_req=0, out=16,
              B=2, T=1, Hq=32, Hkv=8, D=128, page_size=16, max_seq_len=64, window=0, scale=1.0, workspace=16,
