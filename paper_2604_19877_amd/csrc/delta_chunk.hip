@@ -32,6 +32,8 @@
 // buffered with one barrier per chunk.  Each wavefront solves the triangular system for its own
 // columns in four 4-row stages: rows live 4 to a lane, so a stage is a 4x4 solve inside the lanes
 // of one group, a broadcast of its 4 results, and a 4x4 block update in the later groups.
+#include <mutex>
+
 #include "common.h"
 #include "delta_device.h"
 
@@ -696,13 +698,14 @@ sa_status chunk_launch(const char* name, const void* q, const void* k, const voi
   const dim3 grid(static_cast<unsigned>(rows * H));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (KDA) {
-    static bool lds_raised = false;  // more than the default 64 KiB of dynamic LDS must be asked for once
-    if (!lds_raised) {
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kda_chunk_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kKdaLds);
-      if (e != hipSuccess) return sa::fail(SA_EHIP, "%s: %s", name, hipGetErrorString(e));
-      lds_raised = true;
-    }
+    // More than the default 64 KiB of dynamic LDS must be asked for, once.
+    static std::once_flag once;
+    static hipError_t raised = hipSuccess;
+    std::call_once(once, [] {
+      raised = hipFuncSetAttribute(reinterpret_cast<const void*>(kda_chunk_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kKdaLds);
+    });
+    if (raised != hipSuccess) return sa::fail(SA_EHIP, "%s: %s", name, hipGetErrorString(raised));
     sa::launch(SA_K_KDA_CHUNK, kda_chunk_kernel, grid, dim3(256), kKdaLds, s, p);
   } else {
     sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel, grid, dim3(256), 2 * kStageB + 4 * kWaveB, s, p);
