@@ -35,17 +35,16 @@ struct DeltaParams {
 };
 
 // Operands of one step as they arrive from memory (bf16 still packed).
-template <int RPL, bool KDA>
+template <int RPL>
 struct StepOperands {
   uint4 k[RPL / 8], q[RPL / 8];
-  float4 alpha_vec[KDA ? RPL / 4 : 1];
-  float alpha, beta;
+  float alpha, beta;  // alpha: the scalar gate of GDN (KDA's gate vector is fetched apart)
   uint2 v;
 };
 
 template <int DK, int DV, bool KDA>
-__device__ __forceinline__ void load_operands(StepOperands<DK / 8, KDA>& o, const DeltaParams& p, size_t bt, int h, int hk,
-                                              int row0, int col0) {
+__device__ __forceinline__ void load_operands(StepOperands<DK / 8>& o, const DeltaParams& p, size_t bt, int h, int hk, int row0,
+                                              int col0) {
   constexpr int RPL = DK / 8;
   const uint4* kp = reinterpret_cast<const uint4*>(p.k + (bt * p.Hk + hk) * DK + row0);
   const uint4* qp = reinterpret_cast<const uint4*>(p.q + (bt * p.Hk + hk) * DK + row0);
@@ -56,14 +55,15 @@ __device__ __forceinline__ void load_operands(StepOperands<DK / 8, KDA>& o, cons
   }
   o.v = *reinterpret_cast<const uint2*>(p.v + (bt * p.H + h) * DV + col0);
   o.beta = load_uniform(p.beta, bt * p.H + h);
-  if constexpr (KDA) {
-    const float4* ap = reinterpret_cast<const float4*>(p.alpha + (bt * p.H + h) * DK + row0);
+  o.alpha = KDA ? 1.f : load_uniform(p.alpha, bt * p.H + h);
+}
+
+// KDA's gates of this lane's rows for one step.
+template <int DK>
+__device__ __forceinline__ void load_gate_vector(float4 (&a)[DK / 32], const DeltaParams& p, size_t bt, int h, int row0) {
+  const float4* ap = reinterpret_cast<const float4*>(p.alpha + (bt * p.H + h) * DK + row0);
 #pragma unroll
-    for (int i = 0; i < RPL / 4; ++i) o.alpha_vec[i] = ap[i];
-    o.alpha = 1.f;
-  } else {
-    o.alpha = load_uniform(p.alpha, bt * p.H + h);
-  }
+  for (int i = 0; i < DK / 32; ++i) a[i] = ap[i];
 }
 
 template <int N>
@@ -83,7 +83,7 @@ __device__ __forceinline__ void unpack_bf16(const uint4 (&src)[N / 8], float (&d
 // unconditional store.  MULTI = true: any T and n_commit with the tile held in registers; the
 // operands of step t+1 are requested before step t is computed.
 template <int DK, int DV, bool KDA, bool MULTI>
-__global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
+__global__ __launch_bounds__(DV * 2, (KDA && MULTI && DV == 128) ? 3 : 1) void delta_step_kernel(DeltaParams p) {
   constexpr int RPL = DK / 8;  // rows per lane
   const int r = blockIdx.x / p.H;
   const int h = blockIdx.x - r * p.H;
@@ -104,8 +104,10 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
   // All requests first: the small operands of step 0, then the 16 state rows of this lane.  The
   // scheduling barrier keeps the compiler from sinking any of them towards its first use, which
   // would put a full memory latency on the critical path of every tile.
-  StepOperands<RPL, KDA> cur, nxt;
+  StepOperands<RPL> cur, nxt;
+  float4 gate_vec[RPL / 4];  // KDA only: single-buffered, the next step's is requested as soon as this step's is applied
   load_operands<DK, DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0);
+  if constexpr (KDA) load_gate_vector<DK>(gate_vec, p, static_cast<size_t>(b) * T, h, row0);
   float4 s[RPL];
 #pragma unroll
   for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + m * DV);
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
     if constexpr (KDA) {
 #pragma unroll
       for (int i = 0; i < RPL / 4; ++i) {
-        const float4 a = cur.alpha_vec[i];
+        const float4 a = gate_vec[i];
         const float av[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -140,6 +142,9 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
           x.z *= av[e];
           x.w *= av[e];
         }
+      }
+      if constexpr (MULTI) {
+        if (t + 1 < T) load_gate_vector<DK>(gate_vec, p, bt + 1, h, row0);
       }
     } else {
       const float a = cur.alpha;
