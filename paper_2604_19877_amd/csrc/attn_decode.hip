@@ -116,12 +116,11 @@ SplitPlan plan_splits(int n_req, int Hkv, int T, int max_seq_len, int window) {
   return make(best);
 }
 
+// Two floats to a packed bf16 pair (a in the low half), round to nearest even: one v_cvt_pk_bf16_f32.
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
-  // a, b are finite here
-  uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-  ua += 0x7fffu + ((ua >> 16) & 1u);
-  ub += 0x7fffu + ((ub >> 16) & 1u);
-  return (ua >> 16) | (ub & 0xffff0000u);
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
 }
 
 struct PageFrags {
