@@ -171,3 +171,30 @@ def test_chunked_matches_the_one_token_kernel_at_full_shape(kda):
     torch.cuda.synchronize()
     assert rel_err(o, host(out)) <= 2e-4
     assert rel_err(S, host(state)) <= 5e-5
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_prefill_with_chunks_then_decode_token_by_token(kda):
+    """The two kernel families share the state layout: 100 tokens go through the chunked call, the next 12 through
+    the one-token decode kernel on the same state buffer; the oracle runs all 112 steps in one go."""
+    B, H, Hk, T0, T1 = 2, 4, 2, 100, 12
+    p = gen.recurrent_inputs(4800 + kda, B, T0 + T1, H, Hk, 128, 128, kda)
+    S0 = gen.recurrent_state(4801, B * H, 128, 128).reshape(B, H, 128, 128)
+    scale = 128 ** -0.5
+    d = {n: dev(a) for n, a in p.items()}
+    state = dev(S0.copy())
+    out0 = torch.empty((B, T0, H, 128), dtype=torch.float32, device="cuda")
+    FN[kda][0](*[d[n][:, :T0].contiguous() for n in ("q", "k", "v", "alpha", "beta")], state, state, out0, None, None, 0,
+               B, T0, H, Hk, 128, 128, scale)
+    step = sa.kda_decode_step if kda else sa.gdn_decode_step
+    outs = []
+    for t in range(T0, T0 + T1):
+        o = torch.empty((B, 1, H, 128), dtype=torch.float32, device="cuda")
+        step(*[d[n][:, t:t + 1].contiguous() for n in ("q", "k", "v", "alpha", "beta")], state, state, o, None, None, 0,
+             B, 1, H, Hk, 128, 128, scale, 1)
+        outs.append(o)
+    torch.cuda.synchronize()
+    o_all = np.concatenate([host(out0)] + [host(x) for x in outs], axis=1)
+    o_ref, S_ref = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, scale)
+    assert rel_err(o_all, o_ref) <= OUT_TOL
+    assert rel_err(host(state), S_ref) <= STATE_TOL
