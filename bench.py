@@ -246,7 +246,8 @@ def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_
     of each mixer at the batch-64 shapes (same state / KV bytes as a single-token step)."""
     res = {}
     for T in (4, 8):
-        for name, kda, fn, kid in (("gdn", False, sa.gdn_decode_step, sa.SA_K_GDN), ("kda", True, sa.kda_decode_step, sa.SA_K_KDA)):
+        for name, kda, fn, kids in (("gdn", False, sa.gdn_decode_step, (sa.SA_K_GDN, sa.SA_K_GDN_CHUNK)),
+                                    ("kda", True, sa.kda_decode_step, (sa.SA_K_KDA, sa.SA_K_KDA_CHUNK))):
             x = {n: dev(a) for n, a in gen.recurrent_inputs(1900 + kda + T, B, T, H, H, DK, DV, kda).items()}
             states = rec[name][1]
             out = torch.empty((B, T, H, DV), dtype=torch.float32, device="cuda")
@@ -256,7 +257,7 @@ def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_
                    None, None, 0, B, T, H, H, DK, DV, rec_scale, T, stream)
             torch.cuda.synchronize()
             sa.sa_prof_enable(False)
-            _, _, ms = sa.sa_prof_read(kid, reps)
+            ms = [t for kid in kids for t in sa.sa_prof_read(kid, reps)[2]]   # 5 tokens and more run on the chunk kernels
             avg = sum(ms[1:]) / (len(ms) - 1)
             nbytes = alg[name + "_decode_step"]
             res["%s_T%d" % (name, T)] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
@@ -377,7 +378,7 @@ def chunk_cases(torch, sa, T, rec_scale, stream, g, reps=6):
         sa.sa_prof_enable(True)
         for i in range(reps):
             s = states[i % 4]
-            fn(xq, xk, xv, alpha, beta, s, s, out, None, None, 0, B, T, H, H, DK, DV, rec_scale, stream)
+            fn(xq, xk, xv, alpha, beta, s, s, out, None, None, 0, B, T, H, H, DK, DV, rec_scale, stream=stream)
         torch.cuda.synchronize()
         sa.sa_prof_enable(False)
         _, _, ms = sa.sa_prof_read(kid, reps)

@@ -48,14 +48,13 @@ class sa_block_io(ctypes.Structure):
 
 _BLOCK_ARGS = [ctypes.POINTER(sa_block_io)] + [c_void_p] * 5 + [c_int] * 6 + [c_float, c_void_p]
 _RECURRENT_ARGS = [c_void_p] * 10 + [c_int] * 7 + [c_float, c_int, c_void_p]
-_CHUNK_ARGS = [c_void_p] * 10 + [c_int] * 7 + [c_float, c_void_p]
 _SIGNATURES = {
     "sa_last_error": (c_char_p, []),
     "sa_version": (c_int, []),
     "gdn_decode_step": (c_int, _RECURRENT_ARGS),
     "kda_decode_step": (c_int, _RECURRENT_ARGS),
-    "gdn_chunk_steps": (c_int, _CHUNK_ARGS),
-    "kda_chunk_steps": (c_int, _CHUNK_ARGS),
+    "gdn_chunk_steps": (c_int, _RECURRENT_ARGS),
+    "kda_chunk_steps": (c_int, _RECURRENT_ARGS),
     "gdn_block_decode": (c_int, _BLOCK_ARGS),
     "kda_block_decode": (c_int, _BLOCK_ARGS),
     "kv_append": (c_int, [c_void_p] * 4 + [c_int, c_void_p, c_int, c_void_p] + [c_int] * 5 + [c_void_p]),
@@ -156,17 +155,15 @@ def kda_decode_step(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, re
 
 
 def gdn_chunk_steps(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,
-                    stream=None):
-    _check(lib().gdn_chunk_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), _ptr(state_in), _ptr(state_out),
-                                 _ptr(out), _ptr(slot_idx), _ptr(req_idx), n_req, B, T, H, Hk, dk, dv, scale,
-                                 _stream(stream)))
+                    n_commit=None, stream=None):
+    _recurrent(lib().gdn_chunk_steps, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
+               Hk, dk, dv, scale, T if n_commit is None else n_commit, stream)
 
 
 def kda_chunk_steps(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,
-                    stream=None):
-    _check(lib().kda_chunk_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), _ptr(state_in), _ptr(state_out),
-                                 _ptr(out), _ptr(slot_idx), _ptr(req_idx), n_req, B, T, H, Hk, dk, dv, scale,
-                                 _stream(stream)))
+                    n_commit=None, stream=None):
+    _recurrent(lib().kda_chunk_steps, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
+               Hk, dk, dv, scale, T if n_commit is None else n_commit, stream)
 
 
 def make_block_io(**kw):

@@ -45,6 +45,13 @@ sa_status check_attn_decode(const void* q, const void* kpool, const void* vpool,
                             int Hq, int Hkv, int D, int page_size, int max_seq_len, int window, void* workspace,
                             size_t workspace_bytes);
 
+// The chunk-parallel recurrent kernels (16 tokens at a time on the matrix cores), callable under another entry
+// point's name; dry_run checks the arguments and enqueues nothing.
+sa_status chunked_steps(bool kda, bool dry_run, const char* name, const void* q, const void* k, const void* v, const float* alpha,
+                        const float* beta, const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                        const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit,
+                        void* stream);
+
 // Turns the sticky launch error (if any) into a status.
 sa_status check_launch(const char* what);
 

@@ -58,6 +58,7 @@ struct ChunkParams {
   const int32_t* req_idx;
   int T, H, Hk;
   float scale;
+  int n_commit;  // state_out receives the state after this many tokens (0 .. T)
 };
 
 constexpr int kD = 128;          // dk = dv
@@ -143,6 +144,19 @@ __device__ __forceinline__ void readout_rows(f32x4 (&o)[2], const f32x4 (&delta)
     o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.lo), o[c], 0, 0, 0);
     o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
   }
+}
+
+// Writes this lane's part of the state tile (accumulator layout) with the non-temporal hint.  The offset is
+// made opaque so that the 32 store addresses are formed here and not kept in registers from the kernel's start.
+__device__ __forceinline__ void store_tile(const f32x4 (&S)[8][2], float* sout, uint32_t lane_off) {
+  asm volatile("" : "+v"(lane_off));
+#pragma unroll
+  for (int rt = 0; rt < 8; ++rt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x2 x = {S[rt][0][j], S[rt][1][j]};
+      __builtin_nontemporal_store(x, reinterpret_cast<f32x2*>(sout + (lane_off + (16 * rt + j) * kD)));
+    }
 }
 
 // Offsets are formed in bytes in 32 bits so that a load is "scalar base + vector offset".
@@ -233,6 +247,8 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
   const int n_chunks = (p.T + kC - 1) / kC;
   for (int ch = 0; ch < n_chunks; ++ch) {
     const int t0 = ch * kC;
+    const int n_keep = p.n_commit - t0;  // tokens of this chunk that the stored state includes, if it is stored here
+    if (n_keep == 0 && p.n_commit < p.T && (t0 > 0 || sout != sin)) store_tile(S, sout, lane_off);
     unsigned char* const stage = lds + (ch & 1) * kStageB;
     unsigned char* const k_tok = stage;                       // [16 tokens][kTokRowB]
     unsigned char* const q_tok = stage + kC * kTokRowB;
@@ -334,6 +350,44 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       }
     }
 
+    // The stored state ends inside this chunk (a verify pass whose later tokens may be rejected): the same
+    // update with the decay taken up to token n_keep-1 and the later tokens left out, written straight to memory.
+    if (n_keep > 0 && n_keep < kC && p.n_commit < p.T) {
+      uint32_t keep_off = lane_off;
+      asm volatile("" : "+v"(keep_off));
+      const float log_keep = __shfl(log_sum, n_keep - 1);
+      const float g_keep = exp2f(log_keep);
+      Split4x2 dk2[2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        f32x4 x;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float lt = __shfl(log_sum, 4 * g + j);
+          x[j] = 4 * g + j < n_keep ? exp2f(log_keep - lt) * rhs[c][j] : 0.f;
+        }
+        dk2[c] = split2(x);
+      }
+#pragma unroll
+      for (int rt = 0; rt < 8; ++rt) {
+        const s16x4 kt = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g));
+        f32x4 acc[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          acc[c] = S[rt][c];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[c][j] *= g_keep;
+          acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, dk2[c].lo), acc[c], 0, 0, 0);
+          acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, dk2[c].hi), acc[c], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const f32x2 x = {acc[0][j], acc[1][j]};
+          __builtin_nontemporal_store(x, reinterpret_cast<f32x2*>(sout + (keep_off + (16 * rt + j) * kD)));
+        }
+      }
+    }
+
     // S <- g(15,-1) S + K^T (g(15,t) delta_t): rows of the B operand are tokens.
     Split4x2 ds[2];
 #pragma unroll
@@ -360,13 +414,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     // The per-wavefront matrices are rewritten in the next chunk only after this chunk's reads (program order).
   }
 
-#pragma unroll
-  for (int rt = 0; rt < 8; ++rt)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const f32x2 x = {S[rt][0][j], S[rt][1][j]};
-      __builtin_nontemporal_store(x, reinterpret_cast<f32x2*>(sout + (lane_off + (16 * rt + j) * kD)));
-    }
+  if (p.n_commit == p.T) store_tile(S, sout, lane_off);
 }
 
 
@@ -488,6 +536,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
     }
   __builtin_amdgcn_sched_barrier(0);
 
+  if (p.n_commit == 0 && sout != sin) store_tile(S, sout, lane_off);
   const int n_chunks = (p.T + kC - 1) / kC;
   for (int ch = 0; ch < n_chunks; ++ch) {
     const int t0 = ch * kC;
@@ -511,7 +560,11 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
         if (lane == 0) limit[wave] = mine;
       }
       __syncthreads();  // also: every wavefront has finished consuming the previous pass
-      const int stop = __builtin_amdgcn_readfirstlane(min(limit[0], limit[1]));  // the same for all lanes
+      int stop = __builtin_amdgcn_readfirstlane(min(limit[0], limit[1]));  // the same for all lanes
+      // A pass never straddles the token after which the state is stored: that state is then simply the tile
+      // as it stands after the pass.
+      const int n_keep = p.n_commit - t0;
+      if (first < n_keep && n_keep < stop) stop = n_keep;
 
       // (2) Operands of this pass from the raw token this thread fetched.
       {
@@ -659,17 +712,12 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
         }
       }
       first = stop;
+      if (t0 + first == p.n_commit && p.n_commit < p.T) store_tile(S, sout, lane_off);  // first > 0 here
     }
     cur = nxt;
   }
 
-#pragma unroll
-  for (int rt = 0; rt < 8; ++rt)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const f32x2 x = {S[rt][0][j], S[rt][1][j]};
-      __builtin_nontemporal_store(x, reinterpret_cast<f32x2*>(sout + (lane_off + (16 * rt + j) * kD)));
-    }
+  if (p.n_commit == p.T) store_tile(S, sout, lane_off);
 }
 
 }  // namespace
@@ -677,24 +725,27 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
 namespace {
 
 template <bool KDA>
-sa_status chunk_launch(const char* name, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
-                       const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
-                       int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, void* stream) {
+sa_status chunk_launch(bool dry_run, const char* name, const void* q, const void* k, const void* v, const float* alpha,
+                       const float* beta, const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                       const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit,
+                       void* stream) {
   SA_REQUIRE(B >= 0 && T >= 1, SA_EINVAL, "%s: need B >= 0 and T >= 1 (B=%d, T=%d)", name, B, T);
   SA_REQUIRE(H >= 1 && Hk >= 1 && H % Hk == 0, SA_EINVAL, "%s: H must be a positive multiple of Hk (H=%d, Hk=%d)", name, H, Hk);
+  SA_REQUIRE(n_commit >= 0 && n_commit <= T, SA_EINVAL, "%s: n_commit=%d outside [0,T=%d]", name, n_commit, T);
   SA_REQUIRE(dk == kD && dv == kD, SA_EUNSUPPORTED, "%s: (dk,dv)=(%d,%d), only (128,128) is supported", name, dk, dv);
   const int rows = req_idx ? n_req : B;
   SA_REQUIRE(rows >= 0 && rows <= B, SA_EINVAL, "%s: n_req=%d outside [0,B=%d]", name, n_req, B);
   if (rows == 0) return SA_OK;
   SA_REQUIRE(q && k && v && alpha && beta && state_in && state_out && out, SA_EINVAL, "%s: null pointer", name);
   SA_REQUIRE(sa::aligned(q, 16) && sa::aligned(k, 16) && sa::aligned(v, 16) && sa::aligned(state_in, 16) &&
-                 sa::aligned(state_out, 16) && sa::aligned(out, 16) && sa::aligned(alpha, 4) && sa::aligned(beta, 4) &&
+                 sa::aligned(state_out, 16) && sa::aligned(out, 16) && sa::aligned(alpha, KDA ? 16 : 4) && sa::aligned(beta, 4) &&
                  sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4),
              SA_EINVAL, "%s: misaligned pointer", name);
   SA_REQUIRE(static_cast<long long>(rows) * H <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many tiles", name);
+  if (dry_run) return SA_OK;
 
   ChunkParams p{static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
-                alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale};
+                alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale, n_commit};
   const dim3 grid(static_cast<unsigned>(rows * H));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (KDA) {
@@ -715,18 +766,30 @@ sa_status chunk_launch(const char* name, const void* q, const void* k, const voi
 
 }  // namespace
 
+// The chunk-parallel kernels under the names and rules of the decode steps (used by them for longer calls).
+sa_status sa::chunked_steps(bool kda, bool dry_run, const char* name, const void* q, const void* k, const void* v,
+                            const float* alpha, const float* beta, const float* state_in, float* state_out, float* out,
+                            const int32_t* slot_idx, const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
+                            float scale, int n_commit, void* stream) {
+  if (kda)
+    return chunk_launch<true>(dry_run, name, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk,
+                              dk, dv, scale, n_commit, stream);
+  return chunk_launch<false>(dry_run, name, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk,
+                             dk, dv, scale, n_commit, stream);
+}
+
 extern "C" sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                                      const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
-                                     float scale, void* stream) {
-  return chunk_launch<false>("gdn_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
-                             Hk, dk, dv, scale, stream);
+                                     float scale, int n_commit, void* stream) {
+  return chunk_launch<false>(false, "gdn_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B,
+                             T, H, Hk, dk, dv, scale, n_commit, stream);
 }
 
 extern "C" sa_status kda_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                                      const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
-                                     float scale, void* stream) {
-  return chunk_launch<true>("kda_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
-                            Hk, dk, dv, scale, stream);
+                                     float scale, int n_commit, void* stream) {
+  return chunk_launch<true>(false, "kda_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B,
+                            T, H, Hk, dk, dv, scale, n_commit, stream);
 }

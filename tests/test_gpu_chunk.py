@@ -148,7 +148,7 @@ def test_slots_request_list_and_untouched_rows(kda):
 
 @pytest.mark.parametrize("kda", KINDS)
 def test_chunked_matches_the_one_token_kernel_at_full_shape(kda):
-    """Batch 64 x 32 heads, 64 tokens: the chunked call and 64 single steps of the decode kernel agree
+    """Batch 64 x 32 heads, 64 tokens: the chunked call and 16 four-token calls of the decode kernel agree
     (both are checked against the oracle elsewhere; here every tile of the full launch is compared).
     The bounds are half the state tolerance and a tenth of the output tolerance: two rounded bf16 terms
     per fp32 operand leave the chunked path ~1e-5 from the oracle, the fp32 one-token path ~1e-6."""
@@ -161,12 +161,12 @@ def test_chunked_matches_the_one_token_kernel_at_full_shape(kda):
     state = dev(S0.copy())
     out = torch.empty((B, T, H, 128), dtype=torch.float32, device="cuda")
     step = sa.kda_decode_step if kda else sa.gdn_decode_step
-    for c in range(T // 16):
-        sl = slice(16 * c, 16 * c + 16)
-        part = torch.empty((B, 16, H, 128), dtype=torch.float32, device="cuda")
+    for c in range(T // 4):   # 4 tokens per call: the register-resident fp32 kernel
+        sl = slice(4 * c, 4 * c + 4)
+        part = torch.empty((B, 4, H, 128), dtype=torch.float32, device="cuda")
         step(d["q"][:, sl].contiguous(), d["k"][:, sl].contiguous(), d["v"][:, sl].contiguous(),
              d["alpha"][:, sl].contiguous(), d["beta"][:, sl].contiguous(), state, state, part, None, None, 0,
-             B, 16, H, H, 128, 128, scale, 16)
+             B, 4, H, H, 128, 128, scale, 4)
         out[:, sl] = part
     torch.cuda.synchronize()
     assert rel_err(o, host(out)) <= 2e-4
@@ -198,3 +198,52 @@ def test_prefill_with_chunks_then_decode_token_by_token(kda):
     o_ref, S_ref = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, scale)
     assert rel_err(o_all, o_ref) <= OUT_TOL
     assert rel_err(host(state), S_ref) <= STATE_TOL
+
+
+@pytest.mark.parametrize("kda", KINDS)
+@pytest.mark.parametrize("n_commit", [0, 1, 7, 16, 21, 32, 39])
+@pytest.mark.parametrize("in_place", [False, True])
+def test_committed_prefix_of_a_chunked_call(kda, n_commit, in_place):
+    """All 40 outputs are produced, the state written is the one after n_commit tokens (inside a chunk, at a chunk
+    boundary, nothing at all); out of place the input state keeps its bytes."""
+    B, H, T = 2, 2, 40
+    p = gen.recurrent_inputs(4900 + kda + n_commit, B, T, H, H, 128, 128, kda)
+    S0 = gen.recurrent_state(4901, B * H, 128, 128).reshape(B, H, 128, 128)
+    d = {n: dev(a) for n, a in p.items()}
+    s_in = dev(S0.copy())
+    s_out = s_in if in_place else torch.full_like(s_in, float("nan"))
+    out = torch.empty((B, T, H, 128), dtype=torch.float32, device="cuda")
+    FN[kda][0](d["q"], d["k"], d["v"], d["alpha"], d["beta"], s_in, s_out, out, None, None, 0, B, T, H, H, 128, 128, 0.25,
+               n_commit)
+    torch.cuda.synchronize()
+    o_ref, _ = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 0.25)
+    cut = {n: a[:, :n_commit] for n, a in p.items()}
+    S_ref = FN[kda][1](cut["q"], cut["k"], cut["v"], cut["alpha"], cut["beta"], S0, 0.25)[1] if n_commit else S0
+    assert rel_err(host(out), o_ref) <= OUT_TOL
+    assert rel_err(host(s_out), S_ref) <= STATE_TOL
+    if not in_place:
+        assert np.array_equal(host(s_in), S0)
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_decode_step_with_eight_tokens_runs_on_the_chunk_kernels_and_keeps_its_contract(kda):
+    """gdn_decode_step / kda_decode_step hand calls of 5 and more tokens to the chunk-parallel kernels: an 8-token
+    verify with 3 accepted tokens, out of place."""
+    B, H, T, n_commit = 3, 4, 8, 3
+    p = gen.recurrent_inputs(4950 + kda, B, T, H, H, 128, 128, kda)
+    S0 = gen.recurrent_state(4951, B * H, 128, 128).reshape(B, H, 128, 128)
+    d = {n: dev(a) for n, a in p.items()}
+    s_in, s_out = dev(S0.copy()), torch.empty((B, H, 128, 128), dtype=torch.float32, device="cuda")
+    out = torch.empty((B, T, H, 128), dtype=torch.float32, device="cuda")
+    step, kid = (sa.kda_decode_step, sa.SA_K_KDA_CHUNK) if kda else (sa.gdn_decode_step, sa.SA_K_GDN_CHUNK)
+    sa.sa_prof_read(kid)
+    sa.sa_prof_enable(True)
+    step(d["q"], d["k"], d["v"], d["alpha"], d["beta"], s_in, s_out, out, None, None, 0, B, T, H, H, 128, 128, 1.0, n_commit)
+    torch.cuda.synchronize()
+    sa.sa_prof_enable(False)
+    assert sa.sa_prof_read(kid)[0] == 1
+    o_ref, _ = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 1.0)
+    S_ref = FN[kda][1](*[p[n][:, :n_commit] for n in ("q", "k", "v", "alpha", "beta")], S0, 1.0)[1]
+    assert rel_err(host(out), o_ref) <= OUT_TOL
+    assert rel_err(host(s_out), S_ref) <= STATE_TOL
+    assert np.array_equal(host(s_in), S0)
