@@ -32,8 +32,6 @@
 // buffered with one barrier per chunk.  Each wavefront solves the triangular system for its own
 // columns in four 4-row stages: rows live 4 to a lane, so a stage is a 4x4 solve inside the lanes
 // of one group, a broadcast of its 4 results, and a 4x4 block update in the later groups.
-#include <mutex>
-
 #include "common.h"
 #include "delta_device.h"
 
@@ -432,16 +430,17 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
 // those of a trained model a pass is always the whole chunk.
 //
 // Staging per pass, two barriers: (1) 128 threads, one per key channel, run the product of gates down the
-// chunk, write P and 1/P tables and the number of tokens their channel allows; barrier; (2) every thread
+// chunk, write a table of P and the number of tokens their channel allows; barrier; (2) every thread
 // scales the 8 channels of the one token whose raw k and q it fetched (coalesced 16-byte loads), splits
 // and stores them as MFMA operands, token-major for the A operands of the 16x16x32 products and
 // channel-major for K^T Delta; barrier; (3) each wavefront consumes them as in the GDN kernel.
 constexpr int kTabRow = kD;                                // floats per token row of the P and 1/P tables
 constexpr int kKdaTok = 6 * kC * kTokRowB;                 // Khat, Ktil, Qhat x (hi, lo), token-major
 constexpr int kKdaChn = 2 * kD * kChRowB;                  // Kend (hi, lo), channel-major
-constexpr int kKdaTab = 2 * kC * kTabRow * 4;              // P and 1/P
+constexpr int kKdaTab = kC * kTabRow * 4;                  // P
 constexpr int kKdaMisc = kD * 4 + 16;                      // P at the pass's last token per channel; token limits of 2 wavefronts
 constexpr int kKdaLds = kKdaTok + kKdaChn + kKdaTab + kKdaMisc + 4 * kWaveB;
+static_assert(kKdaLds <= 64 * 1024, "the KDA chunk kernel must fit the default dynamic LDS limit");
 constexpr float kMinGate = 7.888609052e-31f;               // 2^-100
 
 struct KdaRaw {
@@ -504,8 +503,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
   unsigned char* const kend_hi = lds + kKdaTok;
   unsigned char* const kend_lo = kend_hi + kD * kChRowB;
   float* const p_tab = reinterpret_cast<float*>(lds + kKdaTok + kKdaChn);   // [16][128] P_t per channel
-  float* const ip_tab = p_tab + kC * kTabRow;                               // [16][128] 1 / P_t
-  float* const p_end = ip_tab + kC * kTabRow;                               // [128] P at the last token of the pass
+  float* const p_end = p_tab + kC * kTabRow;                               // [128] P at the last token of the pass
   int* const limit = reinterpret_cast<int*>(p_end + kD);                    // [2] first token the channels of a wavefront refuse
   float* const wave_mat = reinterpret_cast<float*>(lds + kKdaTok + kKdaChn + kKdaTab + kKdaMisc + wave * kWaveB);
   float* const a_off = wave_mat;
@@ -543,7 +541,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
     const int n_tok = min(kC, p.T - t0);
     int first = 0;  // the pass covers tokens [first, stop) of the chunk
     while (first < n_tok) {
-      // (1) Per channel: running product of gates from `first`, its reciprocal, and where it would drop below 2^-100.
+      // (1) Per channel: running product of gates from `first`, and where it would drop below 2^-100.
       if (tid < kD) {
         // The product keeps running past the token where it leaves the range; those entries are never used.
         float prod = 1.f;
@@ -553,7 +551,6 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
           prod *= t >= first ? gates[t] : 1.f;
           mine = (prod < kMinGate && t > first) ? min(mine, t) : mine;
           p_tab[t * kTabRow + chn] = prod;
-          ip_tab[t * kTabRow + chn] = __builtin_amdgcn_rcpf(prod);
         }
 #pragma unroll
         for (int d = 1; d < 64; d *= 2) mine = min(mine, __shfl_xor(mine, d));
@@ -572,8 +569,6 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
         const bool live = tok >= first && tok < stop;
         const f32x4 pa = *reinterpret_cast<const f32x4*>(p_tab + tok * kTabRow + c8),
                     pb = *reinterpret_cast<const f32x4*>(p_tab + tok * kTabRow + c8 + 4);
-        const f32x4 ia = *reinterpret_cast<const f32x4*>(ip_tab + tok * kTabRow + c8),
-                    ib = *reinterpret_cast<const f32x4*>(ip_tab + tok * kTabRow + c8 + 4);
         const f32x4 ea = *reinterpret_cast<const f32x4*>(p_tab + (stop - 1) * kTabRow + c8),
                     eb = *reinterpret_cast<const f32x4*>(p_tab + (stop - 1) * kTabRow + c8 + 4);
         if (tok == 0) {
@@ -585,7 +580,8 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
         for (int e = 0; e < 8; ++e) {
           const uint32_t kw = raw.kst[e >> 1], qw = raw.qst[e >> 1];
           const float kf = (e & 1) ? bf16_hi(kw) : bf16_lo(kw), qf = (e & 1) ? bf16_hi(qw) : bf16_lo(qw);
-          const float pt = e < 4 ? pa[e & 3] : pb[e & 3], it = e < 4 ? ia[e & 3] : ib[e & 3], pe = e < 4 ? ea[e & 3] : eb[e & 3];
+          const float pt = e < 4 ? pa[e & 3] : pb[e & 3], pe = e < 4 ? ea[e & 3] : eb[e & 3];
+          const float it = __builtin_amdgcn_rcpf(pt);  // garbage for a token outside the pass, which `live` discards
           khat[e] = live ? kf * pt : 0.f;
           ktil[e] = live ? kf * it : 0.f;
           qhat[e] = live ? qf * pt : 0.f;
@@ -749,14 +745,6 @@ sa_status chunk_launch(bool dry_run, const char* name, const void* q, const void
   const dim3 grid(static_cast<unsigned>(rows * H));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (KDA) {
-    // More than the default 64 KiB of dynamic LDS must be asked for, once.
-    static std::once_flag once;
-    static hipError_t raised = hipSuccess;
-    std::call_once(once, [] {
-      raised = hipFuncSetAttribute(reinterpret_cast<const void*>(kda_chunk_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   kKdaLds);
-    });
-    if (raised != hipSuccess) return sa::fail(SA_EHIP, "%s: %s", name, hipGetErrorString(raised));
     sa::launch(SA_K_KDA_CHUNK, kda_chunk_kernel, grid, dim3(256), kKdaLds, s, p);
   } else {
     sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel, grid, dim3(256), 2 * kStageB + 4 * kWaveB, s, p);
