@@ -14,14 +14,16 @@ from test_gpu_placement import D, DK, DV, H, HKV, HQ, build_stack
 pytestmark = pytest.mark.gpu
 
 
-def test_placement_step_replays_from_a_graph():
+@pytest.mark.parametrize("T", [1, 8])
+def test_placement_step_replays_from_a_graph(T):
+    """T = 8 is a verify pass: two query tiles in attention, the chunk-parallel kernels for the recurrent mixers."""
     L, B, ctx, window, max_pages = 8, 6, 700, 128, 48
     placements = [gen.placement_string(8001 + i, L) for i in range(3)]
     pid = np.arange(B, dtype=np.int32) % 3
-    layers = build_stack(8100, L, B, 1, ctx, max_pages)
+    layers = build_stack(8100, L, B, T, ctx, max_pages)
     plan = sa.placement_plan_create(placements, pid)
     shapes = sa.sa_shapes(H, H, DK, DV, HQ, HKV, D, 16)
-    ws_bytes = sa.placement_workspace_bytes(plan, shapes, 1, ctx, window)
+    ws_bytes = sa.placement_workspace_bytes(plan, shapes, T, ctx, window)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
     keep, ios = [], []
     for io in layers:
@@ -29,7 +31,7 @@ def test_placement_step_replays_from_a_graph():
         t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
         t["state0"] = dev(io["state"].copy())
         t["state"], t["kpool"], t["vpool"] = dev(io["state"].copy()), dev(kphys), dev(vphys)
-        t["out"] = torch.zeros((B, 1, H, DV), dtype=torch.float32, device="cuda")
+        t["out"] = torch.zeros((B, T, H, DV), dtype=torch.float32, device="cuda")
         keep.append(t)
         ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"], alpha_vec=t["alpha_vec"],
                                     beta=t["beta"], state=t["state"], q_attn=t["qa"], kpool=t["kpool"], vpool=t["vpool"],
@@ -43,7 +45,7 @@ def test_placement_step_replays_from_a_graph():
             t["out"].zero_()
 
     def step(stream=None):
-        sa.placement_decode(plan, io_arr, shapes, 1, window, D ** -0.5, DK ** -0.5, ws, ws_bytes, stream)
+        sa.placement_decode(plan, io_arr, shapes, T, window, D ** -0.5, DK ** -0.5, ws, ws_bytes, stream)
 
     reset()
     step()
