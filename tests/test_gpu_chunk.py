@@ -247,3 +247,32 @@ def test_decode_step_with_eight_tokens_runs_on_the_chunk_kernels_and_keeps_its_c
     assert rel_err(host(out), o_ref) <= OUT_TOL
     assert rel_err(host(s_out), S_ref) <= STATE_TOL
     assert np.array_equal(host(s_in), S0)
+
+
+@pytest.mark.parametrize("kda", KINDS)
+def test_long_prefill_full_batch_sampled_tiles(kda):
+    """64 sequences x 32 heads x 512 tokens in one call (the shape bench.py --prefill times); the oracle follows a
+    seeded sample of tiles through all 512 steps."""
+    B, H, T = 64, 32, 512
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4990 + kda)
+    nrm = lambda x: (x / x.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    q = nrm(torch.empty((B, T, H, 128), device="cuda").normal_(generator=g))
+    k = nrm(torch.empty((B, T, H, 128), device="cuda").normal_(generator=g))
+    v = torch.empty((B, T, H, 128), device="cuda").normal_(generator=g).bfloat16()
+    beta = torch.sigmoid(torch.empty((B, T, H), device="cuda").normal_(generator=g))
+    alpha = torch.exp(-torch.nn.functional.softplus(
+        torch.empty((B, T, H, 128) if kda else (B, T, H), device="cuda").normal_(generator=g) + 2.0))
+    S0 = torch.empty((B, H, 128, 128), device="cuda").normal_(0.0, 0.02, generator=g)
+    state = S0.clone()
+    out = torch.empty((B, T, H, 128), dtype=torch.float32, device="cuda")
+    FN[kda][0](q, k, v, alpha, beta, state, state, out, None, None, 0, B, T, H, H, 128, 128, 128 ** -0.5)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4991)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    for b, h in [(0, 0), (B - 1, H - 1)] + [(int(rng.integers(B)), int(rng.integers(H))) for _ in range(6)]:
+        sl = (slice(b, b + 1), slice(None), slice(h, h + 1))
+        o_ref, S_ref = FN[kda][1](bits(q[sl]), bits(k[sl]), bits(v[sl]), alpha[sl].cpu().numpy(), beta[sl].cpu().numpy(),
+                                  S0[b:b + 1, h:h + 1].cpu().numpy(), 128 ** -0.5)
+        assert rel_err(host(out[sl]), o_ref) <= OUT_TOL, (b, h)
+        assert rel_err(host(state[b:b + 1, h:h + 1]), S_ref) <= STATE_TOL, (b, h)
