@@ -74,6 +74,15 @@ sa_status kda_decode_step(const void* q, const void* k, const void* v, const flo
                           const int32_t* slot_idx, const int32_t* req_idx, int n_req,
                           int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream);
 
+/* State tiles.  A recurrent state is dk*dv fp32 values per (slot, head); callers that do not want to depend on the
+ * order inside a tile convert with these (Appendix B: "a state matrix S in R^{dk x dv}" per head).  In this library a
+ * tile is plain row-major [dk][dv] (key channel major), so both conversions are copies; they exist so that the order
+ * can change without breaking callers.  rowmajor and tiles: device pointers, n_tiles * dk * dv floats each, 16-byte
+ * aligned, not overlapping.  (dk,dv) as for the decode steps. */
+size_t    sa_state_tile_bytes(int dk, int dv);   /* dk * dv * 4, or 0 for an unsupported shape */
+sa_status sa_state_pack(const float* rowmajor, float* tiles, int n_tiles, int dk, int dv, void* stream);
+sa_status sa_state_unpack(const float* tiles, float* rowmajor, int n_tiles, int dk, int dv, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Many tokens per state pass: the same recurrences and read-out as gdn_decode_step / kda_decode_step,
  * evaluated in their chunk-parallel form (Appendix B: GDN runs "chunkwise" on a WY representation, KDA on

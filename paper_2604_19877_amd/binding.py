@@ -82,6 +82,9 @@ _SIGNATURES = {
     "sa_prof_enable": (None, [c_int]),
     "sa_prof_read": (c_int, [c_int, ctypes.POINTER(c_int), ctypes.POINTER(c_float), ctypes.POINTER(c_float), c_int]),
     "sa_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
+    "sa_state_tile_bytes": (c_size_t, [c_int, c_int]),
+    "sa_state_pack": (c_int, [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]),
+    "sa_state_unpack": (c_int, [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -320,3 +323,15 @@ def sa_prof_read(kernel, capacity=0):
 
 def sa_copy_bytes(src, dst, n_bytes, stream=None):
     _check(lib().sa_copy_bytes(_ptr(src), _ptr(dst), n_bytes, _stream(stream)))
+
+
+def sa_state_tile_bytes(dk, dv) -> int:
+    return lib().sa_state_tile_bytes(dk, dv)
+
+
+def sa_state_pack(rowmajor, tiles, n_tiles, dk, dv, stream=None):
+    _check(lib().sa_state_pack(_ptr(rowmajor), _ptr(tiles), n_tiles, dk, dv, _stream(stream)))
+
+
+def sa_state_unpack(tiles, rowmajor, n_tiles, dk, dv, stream=None):
+    _check(lib().sa_state_unpack(_ptr(tiles), _ptr(rowmajor), n_tiles, dk, dv, _stream(stream)))

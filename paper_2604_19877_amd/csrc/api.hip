@@ -102,3 +102,40 @@ extern "C" sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, v
              static_cast<uint4*>(dst), n16);
   return sa::check_launch("sa_copy_bytes");
 }
+
+namespace {
+
+bool state_shape_ok(int dk, int dv) { return (dk == 64 && dv == 64) || (dk == 128 && dv == 128); }
+
+// Both directions are the same copy while a tile is row-major [dk][dv].
+sa_status state_convert(const char* name, const float* src, float* dst, int n_tiles, int dk, int dv, void* stream) {
+  SA_REQUIRE(state_shape_ok(dk, dv), SA_EUNSUPPORTED, "%s: (dk,dv)=(%d,%d) not in {(64,64),(128,128)}", name, dk, dv);
+  SA_REQUIRE(n_tiles >= 0, SA_EINVAL, "%s: n_tiles=%d is negative", name, n_tiles);
+  if (n_tiles == 0) return SA_OK;
+  SA_REQUIRE(src && dst, SA_EINVAL, "%s: null pointer", name);
+  SA_REQUIRE(sa::aligned(src, 16) && sa::aligned(dst, 16), SA_EINVAL, "%s: misaligned pointer", name);
+  const size_t n_bytes = static_cast<size_t>(n_tiles) * dk * dv * sizeof(float);
+  const char* a = reinterpret_cast<const char*>(src);
+  const char* b = reinterpret_cast<const char*>(dst);
+  SA_REQUIRE(a + n_bytes <= b || b + n_bytes <= a, SA_EINVAL, "%s: source and destination overlap", name);
+  const size_t n16 = n_bytes / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  sa::launch(SA_K_COPY, copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream),
+             reinterpret_cast<const uint4*>(src), reinterpret_cast<uint4*>(dst), n16);
+  return sa::check_launch(name);
+}
+
+}  // namespace
+
+extern "C" size_t sa_state_tile_bytes(int dk, int dv) {
+  return state_shape_ok(dk, dv) ? static_cast<size_t>(dk) * dv * sizeof(float) : 0;
+}
+
+extern "C" sa_status sa_state_pack(const float* rowmajor, float* tiles, int n_tiles, int dk, int dv, void* stream) {
+  return state_convert("sa_state_pack", rowmajor, tiles, n_tiles, dk, dv, stream);
+}
+
+extern "C" sa_status sa_state_unpack(const float* tiles, float* rowmajor, int n_tiles, int dk, int dv, void* stream) {
+  return state_convert("sa_state_unpack", tiles, rowmajor, n_tiles, dk, dv, stream);
+}

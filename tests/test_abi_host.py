@@ -115,3 +115,16 @@ def test_placement_plan_errors():
         with pytest.raises(sa.SaError) as e:
             sa.placement_plan_create(placements, ids)
         assert e.value.status == sa.SA_EINVAL
+
+
+def test_state_tile_helpers_check_their_arguments():
+    assert sa.sa_state_tile_bytes(128, 128) == 65536 and sa.sa_state_tile_bytes(64, 64) == 16384
+    assert sa.sa_state_tile_bytes(96, 96) == 0
+    for fn in (sa.sa_state_pack, sa.sa_state_unpack):
+        fn(16, 1 << 20, 0, 128, 128, 0)                            # nothing to convert (stream 0: no GPU is touched)
+        for bad, status in (((16, 1 << 20, 1, 96, 96), sa.SA_EUNSUPPORTED), ((None, 1 << 20, 1, 128, 128), sa.SA_EINVAL),
+                            ((16, 1 << 20, -1, 128, 128), sa.SA_EINVAL), ((8, 1 << 20, 1, 128, 128), sa.SA_EINVAL),
+                            ((1 << 20, (1 << 20) + 65536, 2, 128, 128), sa.SA_EINVAL)):   # the last one overlaps
+            with pytest.raises(sa.SaError) as e:
+                fn(*bad, 0)
+            assert e.value.status == status, bad

@@ -137,3 +137,22 @@ def test_identities_on_the_gpu(kda):
         sa.kda_decode_step(dg["q"], dg["k"], dg["v"], dev(a_vec), dg["beta"], s2, s2, o2, None, None, 0, B, 1, H, H, dk, dv, 0.5, 1)
         torch.cuda.synchronize()
         assert torch.equal(s1, s2) and torch.equal(o1, o2)
+
+
+def test_state_pack_and_unpack_round_trip_and_feed_a_step():
+    """A state written through sa_state_pack steps exactly like the same numbers uploaded directly, and
+    sa_state_unpack returns the row-major [dk][dv] matrices the oracle works with."""
+    B, H, dk, dv = 2, 4, 128, 128
+    p = gen.recurrent_inputs(1500, B, 1, H, H, dk, dv, False)
+    S0 = gen.recurrent_state(1501, B * H, dk, dv).reshape(B, H, dk, dv)
+    assert sa.sa_state_tile_bytes(dk, dv) == dk * dv * 4
+    rowmajor, tiles, back = dev(S0.copy()), torch.empty((B, H, dk, dv), device="cuda"), torch.empty((B, H, dk, dv), device="cuda")
+    sa.sa_state_pack(rowmajor, tiles, B * H, dk, dv)
+    d = {n: dev(a) for n, a in p.items()}
+    out = torch.empty((B, 1, H, dv), dtype=torch.float32, device="cuda")
+    sa.gdn_decode_step(d["q"], d["k"], d["v"], d["alpha"], d["beta"], tiles, tiles, out, None, None, 0, B, 1, H, H, dk, dv, 1.0, 1)
+    sa.sa_state_unpack(tiles, back, B * H, dk, dv)
+    torch.cuda.synchronize()
+    o_ref, S_ref = om.gdn_steps(p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 1.0)
+    assert rel_err(host(out), o_ref) <= OUT_TOL
+    assert rel_err(host(back), S_ref) <= STATE_TOL
