@@ -140,7 +140,7 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     copy_entry = None
-    if args.copy_calibration:
+    if args.copy_calibration or not args.no_extras:   # the plain copy's GB/s is reported beside the kernels' as a reference
         n_copy = 1 << 30
         src = torch.empty(n_copy, dtype=torch.uint8, device="cuda")
         dst = torch.empty(n_copy, dtype=torch.uint8, device="cuda")
