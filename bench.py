@@ -310,6 +310,22 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
             res["%s_b%d_back_to_back" % (name, nb)] = {
                 "avg_us": round(avg * 1e3, 2), "tokens_per_s": round(nb / (avg * 1e-3), 1),
                 "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            if kda and nb == 64:
+                # what the step's access pattern reaches with no arithmetic: the same tiles read only, written only,
+                # and read + written back, launched back to back like the steps above
+                tile_bytes = nb * H * DK * DV * 4
+                for kind, label, passes in ((0, "read", 1), (1, "write", 1), (2, "read_write", 2)):
+                    sa.sa_prof_enable(True)
+                    for i in range(reps):
+                        sa.sa_stream_tiles(kind, states[i % sets], nb * H, stream)
+                    torch.cuda.synchronize()
+                    sa.sa_prof_enable(False)
+                    _, _, ms = sa.sa_prof_read(sa.SA_K_STREAM, reps)
+                    avg = sum(ms[2:]) / (len(ms) - 2)
+                    res["state_tiles_%s_only_b64" % label] = {
+                        "avg_us": round(avg * 1e3, 2), "bytes": passes * tile_bytes,
+                        "GBps": round(passes * tile_bytes / (avg * 1e-3) / 1e9, 1),
+                        "frac_hbm_peak": round(passes * tile_bytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
             del states
     # whole-block step: convolution + SiLU, L2 norm, gates, state update and gated RMS norm in one launch
     for name, kda, fn, kid in (("gdn", False, sa.gdn_block_decode, sa.SA_K_GDN_BLOCK), ("kda", True, sa.kda_block_decode, sa.SA_K_KDA_BLOCK)):

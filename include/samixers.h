@@ -288,7 +288,7 @@ sa_status sa_pool_layer_tables(const sa_pool* pool, const int32_t* seq_ids, int 
  * Measurement helpers (not part of the method).
  */
 enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5,
-       SA_K_GDN_BLOCK = 6, SA_K_KDA_BLOCK = 7, SA_K_GDN_CHUNK = 8, SA_K_KDA_CHUNK = 9, SA_K_COUNT = 10 };
+       SA_K_GDN_BLOCK = 6, SA_K_KDA_BLOCK = 7, SA_K_GDN_CHUNK = 8, SA_K_KDA_CHUNK = 9, SA_K_STREAM = 10, SA_K_COUNT = 11 };
 /* While enabled, every launch of the kernels above carries HIP start/stop events on its stream that
  * are stamped with the begin and end of the kernel itself. */
 void sa_prof_enable(int on);
@@ -298,6 +298,12 @@ void sa_prof_enable(int on);
 sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms, float* ms_each, int capacity);
 /* Plain streaming copy of n_bytes (multiple of 16) used to calibrate bandwidth counters. */
 sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, void* stream);
+/* The memory traffic of a recurrent decode step at 128x128 without its arithmetic, to measure what the access
+ * pattern itself can reach: one workgroup per 64 KiB tile of `tiles` (device, n_tiles * 16384 floats, 16-byte
+ * aligned), lane pattern and cache hints of the step kernel.  kind 0 reads every tile, 1 overwrites every tile
+ * with a constant, 2 reads each tile, scales it by 0.999 and writes it back.  SA_EINVAL on another kind, a
+ * negative count, a null or misaligned pointer. */
+sa_status sa_stream_tiles(int kind, float* tiles, int n_tiles, void* stream);
 
 #ifdef __cplusplus
 }

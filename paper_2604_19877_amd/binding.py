@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libsamixers.so")
 
 SA_OK, SA_EINVAL, SA_EUNSUPPORTED, SA_EHIP, SA_EWORKSPACE, SA_ENOMEM = 0, -1, -2, -3, -4, -5
 (SA_K_GDN, SA_K_KDA, SA_K_ATTN_SPLIT, SA_K_ATTN_MERGE, SA_K_KV_APPEND, SA_K_COPY, SA_K_GDN_BLOCK, SA_K_KDA_BLOCK,
- SA_K_GDN_CHUNK, SA_K_KDA_CHUNK) = range(10)
+ SA_K_GDN_CHUNK, SA_K_KDA_CHUNK, SA_K_STREAM) = range(11)
 
 
 class SaError(RuntimeError):
@@ -82,6 +82,7 @@ _SIGNATURES = {
     "sa_prof_enable": (None, [c_int]),
     "sa_prof_read": (c_int, [c_int, ctypes.POINTER(c_int), ctypes.POINTER(c_float), ctypes.POINTER(c_float), c_int]),
     "sa_copy_bytes": (c_int, [c_void_p, c_void_p, c_size_t, c_void_p]),
+    "sa_stream_tiles": (c_int, [c_int, c_void_p, c_int, c_void_p]),
     "sa_state_tile_bytes": (c_size_t, [c_int, c_int]),
     "sa_state_pack": (c_int, [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]),
     "sa_state_unpack": (c_int, [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]),
@@ -323,6 +324,10 @@ def sa_prof_read(kernel, capacity=0):
 
 def sa_copy_bytes(src, dst, n_bytes, stream=None):
     _check(lib().sa_copy_bytes(_ptr(src), _ptr(dst), n_bytes, _stream(stream)))
+
+
+def sa_stream_tiles(kind, tiles, n_tiles, stream=None):
+    _check(lib().sa_stream_tiles(kind, _ptr(tiles), n_tiles, _stream(stream)))
 
 
 def sa_state_tile_bytes(dk, dv) -> int:

@@ -1,8 +1,9 @@
-// Error reporting, launch profiling and the calibration copy kernel of libsamixers.
+// Error reporting, launch profiling and the calibration kernels (plain copy, tile streams) of libsamixers.
 #include <mutex>
 #include <vector>
 
 #include "common.h"
+#include "delta_device.h"
 
 namespace {
 
@@ -101,6 +102,60 @@ extern "C" sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, v
   sa::launch(SA_K_COPY, copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, static_cast<const uint4*>(src),
              static_cast<uint4*>(dst), n16);
   return sa::check_launch("sa_copy_bytes");
+}
+
+namespace {
+
+// The memory traffic of the recurrent decode step and nothing else: one workgroup per 64 KiB tile, the lane
+// pattern and non-temporal accesses of delta_step_kernel (lane (r8, c8) of wavefront w owns columns
+// 32w + 4c8 .. +3 of rows 16 r8 .. 16 r8 + 15).  KIND 0 reads the tile, 1 writes it, 2 reads, scales and writes it back.
+template <int KIND>
+__global__ __launch_bounds__(256) void stream_tiles_kernel(float* tiles, float factor) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c8 = lane & 7, r8 = lane >> 3;
+  float* p = tiles + static_cast<size_t>(blockIdx.x) * (128 * 128) + (r8 * 16) * 128 + wave * 32 + c8 * 4;
+  float4 s[16];
+  if (KIND != 1) {
+#pragma unroll
+    for (int m = 0; m < 16; ++m) s[m] = load_state(p + m * 128);
+  }
+  if (KIND == 0) {
+    float acc = 0.f;
+#pragma unroll
+    for (int m = 0; m < 16; ++m) acc += (s[m].x + s[m].y) + (s[m].z + s[m].w);
+    if (acc == factor) p[0] = acc;  // keeps the loads alive; `factor` is chosen so that this never holds
+    return;
+  }
+#pragma unroll
+  for (int m = 0; m < 16; ++m) {
+    if (KIND == 1) {
+      s[m] = float4{factor, factor, factor, factor};
+    } else {
+      s[m].x *= factor;
+      s[m].y *= factor;
+      s[m].z *= factor;
+      s[m].w *= factor;
+    }
+    store_state(p + m * 128, s[m]);
+  }
+}
+
+}  // namespace
+
+extern "C" sa_status sa_stream_tiles(int kind, float* tiles, int n_tiles, void* stream) {
+  SA_REQUIRE(kind >= 0 && kind <= 2, SA_EINVAL, "sa_stream_tiles: kind=%d not in {0 read, 1 write, 2 read-modify-write}", kind);
+  SA_REQUIRE(n_tiles >= 0, SA_EINVAL, "sa_stream_tiles: n_tiles=%d is negative", n_tiles);
+  if (n_tiles == 0) return SA_OK;
+  SA_REQUIRE(tiles && sa::aligned(tiles, 16), SA_EINVAL, "sa_stream_tiles: null or misaligned pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid(static_cast<unsigned>(n_tiles));
+  if (kind == 0)
+    sa::launch(SA_K_STREAM, stream_tiles_kernel<0>, grid, dim3(256), 0, s, tiles, 3.0e38f);
+  else if (kind == 1)
+    sa::launch(SA_K_STREAM, stream_tiles_kernel<1>, grid, dim3(256), 0, s, tiles, 0.01f);
+  else
+    sa::launch(SA_K_STREAM, stream_tiles_kernel<2>, grid, dim3(256), 0, s, tiles, 0.999f);
+  return sa::check_launch("sa_stream_tiles");
 }
 
 namespace {

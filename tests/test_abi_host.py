@@ -128,3 +128,13 @@ def test_state_tile_helpers_check_their_arguments():
             with pytest.raises(sa.SaError) as e:
                 fn(*bad, 0)
             assert e.value.status == status, bad
+
+
+def test_stream_tiles_checks_its_arguments():
+    for bad in (dict(kind=3), dict(kind=-1), dict(n_tiles=-1), dict(tiles=None), dict(tiles=8)):
+        a = dict(kind=0, tiles=16, n_tiles=4, stream=0)
+        a.update(bad)
+        with pytest.raises(sa.SaError) as e:
+            sa.sa_stream_tiles(**a)
+        assert e.value.status == sa.SA_EINVAL, bad
+    sa.sa_stream_tiles(2, 16, 0, 0)   # no tiles: nothing to do, no error

@@ -156,3 +156,22 @@ def test_state_pack_and_unpack_round_trip_and_feed_a_step():
     o_ref, S_ref = om.gdn_steps(p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 1.0)
     assert rel_err(host(out), o_ref) <= OUT_TOL
     assert rel_err(host(back), S_ref) <= STATE_TOL
+
+
+def test_stream_tiles_calibration_kernel_touches_exactly_its_tiles():
+    """The bandwidth-calibration kernel reads, fills or rescales n_tiles tiles of 128x128 and nothing beyond them."""
+    n, guard = 5, 1024
+    buf = torch.empty(n * 128 * 128 + 2 * guard, dtype=torch.float32, device="cuda").normal_()
+    before = buf.clone()
+    tiles = buf[guard:guard + n * 128 * 128]
+    sa.sa_stream_tiles(0, tiles, n)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
+    sa.sa_stream_tiles(2, tiles, n)
+    torch.cuda.synchronize()
+    assert torch.equal(tiles, before[guard:-guard] * 0.999)
+    sa.sa_stream_tiles(1, tiles, n - 1)
+    torch.cuda.synchronize()
+    assert torch.equal(tiles[:(n - 1) * 128 * 128], torch.full(((n - 1) * 128 * 128,), 0.01, device="cuda"))
+    assert torch.equal(tiles[(n - 1) * 128 * 128:], before[guard + (n - 1) * 128 * 128:-guard] * 0.999)
+    assert torch.equal(buf[:guard], before[:guard]) and torch.equal(buf[-guard:], before[-guard:])
