@@ -288,7 +288,7 @@ sa_status sa_pool_layer_tables(const sa_pool* pool, const int32_t* seq_ids, int 
  * Measurement helpers (not part of the method).
  */
 enum { SA_K_GDN = 0, SA_K_KDA = 1, SA_K_ATTN_SPLIT = 2, SA_K_ATTN_MERGE = 3, SA_K_KV_APPEND = 4, SA_K_COPY = 5,
-       SA_K_GDN_BLOCK = 6, SA_K_KDA_BLOCK = 7, SA_K_GDN_CHUNK = 8, SA_K_KDA_CHUNK = 9, SA_K_STREAM = 10, SA_K_COUNT = 11 };
+       SA_K_GDN_BLOCK = 6, SA_K_KDA_BLOCK = 7, SA_K_GDN_CHUNK = 8, SA_K_KDA_CHUNK = 9, SA_K_STREAM = 10, SA_K_LAYER = 11, SA_K_COUNT = 12 };
 /* While enabled, every launch of the kernels above carries HIP start/stop events on its stream that
  * are stamped with the begin and end of the kernel itself. */
 void sa_prof_enable(int on);

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libsamixers.so")
 
 SA_OK, SA_EINVAL, SA_EUNSUPPORTED, SA_EHIP, SA_EWORKSPACE, SA_ENOMEM = 0, -1, -2, -3, -4, -5
 (SA_K_GDN, SA_K_KDA, SA_K_ATTN_SPLIT, SA_K_ATTN_MERGE, SA_K_KV_APPEND, SA_K_COPY, SA_K_GDN_BLOCK, SA_K_KDA_BLOCK,
- SA_K_GDN_CHUNK, SA_K_KDA_CHUNK, SA_K_STREAM) = range(11)
+ SA_K_GDN_CHUNK, SA_K_KDA_CHUNK, SA_K_STREAM, SA_K_LAYER) = range(12)
 
 
 class SaError(RuntimeError):

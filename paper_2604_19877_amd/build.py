@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsamixers.so")
-SOURCES = ["api.hip", "delta_step.hip", "delta_block.hip", "delta_chunk.hip", "attn_decode.hip", "placement.hip", "pool.hip"]
+SOURCES = ["api.hip", "delta_step.hip", "delta_block.hip", "delta_chunk.hip", "attn_decode.hip", "layer_fused.hip", "placement.hip", "pool.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

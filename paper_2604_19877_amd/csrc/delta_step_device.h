@@ -1,0 +1,222 @@
+// Device side of the one-token (and register-resident multi-token) gated delta-rule step, shared by the
+// stand-alone kernels of delta_step.hip and the fused per-layer kernel of layer_fused.hip.
+#pragma once
+#include "delta_device.h"
+#include "samixers.h"
+
+namespace sa {
+
+// Arguments of one recurrent step launch.
+struct DeltaParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  const float* alpha;
+  const float* beta;
+  const float* state_in;
+  float* state_out;
+  float* out;
+  const int32_t* slot_idx;
+  const int32_t* req_idx;
+  int T, H, Hk;
+  float scale;
+  int n_commit;
+};
+
+// One prepared recurrent step: rows = request rows to launch over (0: nothing to do, or the call runs on the
+// chunk-parallel kernels, which `chunked` then says).
+struct DeltaLaunch {
+  DeltaParams p;
+  int rows;
+  bool chunked;
+};
+
+// Argument checks of gdn_decode_step / kda_decode_step; on success with `launch` not null, fills it (defined in
+// delta_step.hip).
+sa_status delta_prepare(bool kda, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                        const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
+                        int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, DeltaLaunch* launch);
+
+}  // namespace sa
+
+namespace {
+
+using sa::DeltaParams;
+
+// Operands of one step as they arrive from memory (bf16 still packed).
+template <int RPL>
+struct StepOperands {
+  uint4 k[RPL / 8], q[RPL / 8];
+  float alpha, beta;  // alpha: the scalar gate of GDN (KDA's gate vector is fetched apart)
+  uint2 v;
+};
+
+template <int DK, int DV, bool KDA>
+__device__ __forceinline__ void load_operands(StepOperands<DK / 8>& o, const DeltaParams& p, size_t bt, int h, int hk, int row0,
+                                              int col0) {
+  constexpr int RPL = DK / 8;
+  const uint4* kp = reinterpret_cast<const uint4*>(p.k + (bt * p.Hk + hk) * DK + row0);
+  const uint4* qp = reinterpret_cast<const uint4*>(p.q + (bt * p.Hk + hk) * DK + row0);
+#pragma unroll
+  for (int i = 0; i < RPL / 8; ++i) {
+    o.k[i] = kp[i];
+    o.q[i] = qp[i];
+  }
+  o.v = *reinterpret_cast<const uint2*>(p.v + (bt * p.H + h) * DV + col0);
+  o.beta = load_uniform(p.beta, bt * p.H + h);
+  o.alpha = KDA ? 1.f : load_uniform(p.alpha, bt * p.H + h);
+}
+
+// KDA's gates of this lane's rows for one step.
+template <int DK>
+__device__ __forceinline__ void load_gate_vector(float4 (&a)[DK / 32], const DeltaParams& p, size_t bt, int h, int row0) {
+  const float4* ap = reinterpret_cast<const float4*>(p.alpha + (bt * p.H + h) * DK + row0);
+#pragma unroll
+  for (int i = 0; i < DK / 32; ++i) a[i] = ap[i];
+}
+
+template <int N>
+__device__ __forceinline__ void unpack_bf16(const uint4 (&src)[N / 8], float (&dst)[N]) {
+#pragma unroll
+  for (int i = 0; i < N / 8; ++i) {
+    const uint32_t w[4] = {src[i].x, src[i].y, src[i].z, src[i].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      dst[8 * i + 2 * e] = bf16_lo(w[e]);
+      dst[8 * i + 2 * e + 1] = bf16_hi(w[e]);
+    }
+  }
+}
+
+// MULTI = false: exactly one committed step (T == 1, n_commit == 1), the decode hot path, with an
+// unconditional store.  MULTI = true: any T and n_commit with the tile held in registers; the
+// operands of step t+1 are requested before step t is computed.
+// The work of one workgroup (2*DV threads): tile `block` = (row of the request list) * H + head.
+template <int DK, int DV, bool KDA, bool MULTI>
+__device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int block) {
+  constexpr int RPL = DK / 8;  // rows per lane
+  const int r = block / p.H;
+  const int h = block - r * p.H;
+  const int b = p.req_idx ? p.req_idx[r] : r;
+  const int slot = p.slot_idx ? p.slot_idx[b] : b;
+  const int hk = h / (p.H / p.Hk);
+  const int wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int c8 = lane & 7, r8 = lane >> 3;
+  const int row0 = r8 * RPL;
+  const int col0 = wave * 32 + c8 * 4;
+  const int T = MULTI ? p.T : 1;
+
+  const size_t tile = (static_cast<size_t>(slot) * p.H + h) * (DK * DV);
+  const float* sin = p.state_in + tile + static_cast<size_t>(row0) * DV + col0;
+  float* sout = p.state_out + tile + static_cast<size_t>(row0) * DV + col0;
+
+  // All requests first: the small operands of step 0, then the 16 state rows of this lane.  The
+  // scheduling barrier keeps the compiler from sinking any of them towards its first use, which
+  // would put a full memory latency on the critical path of every tile.
+  StepOperands<RPL> cur, nxt;
+  float4 gate_vec[RPL / 4];  // KDA only: single-buffered, the next step's is requested as soon as this step's is applied
+  load_operands<DK, DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0);
+  if constexpr (KDA) load_gate_vector<DK>(gate_vec, p, static_cast<size_t>(b) * T, h, row0);
+  float4 s[RPL];
+#pragma unroll
+  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + m * DV);
+  __builtin_amdgcn_sched_barrier(0);
+
+  if (MULTI && p.n_commit == 0 && p.state_out != p.state_in) {
+#pragma unroll
+    for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
+  }
+
+  for (int t = 0; t < T; ++t) {
+    const size_t bt = static_cast<size_t>(b) * T + t;
+    if constexpr (MULTI) {
+      if (t + 1 < T) load_operands<DK, DV, KDA>(nxt, p, bt + 1, h, hk, row0, col0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    float kf[RPL], qf[RPL];
+    unpack_bf16<RPL>(cur.k, kf);
+    unpack_bf16<RPL>(cur.q, qf);
+    const float beta = cur.beta;
+
+    if constexpr (KDA) {
+#pragma unroll
+      for (int i = 0; i < RPL / 4; ++i) {
+        const float4 a = gate_vec[i];
+        const float av[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float4& x = s[4 * i + e];
+          x.x *= av[e];
+          x.y *= av[e];
+          x.z *= av[e];
+          x.w *= av[e];
+        }
+      }
+      if constexpr (MULTI) {
+        if (t + 1 < T) load_gate_vector<DK>(gate_vec, p, bt + 1, h, row0);
+      }
+    } else {
+      const float a = cur.alpha;
+#pragma unroll
+      for (int m = 0; m < RPL; ++m) {
+        s[m].x *= a;
+        s[m].y *= a;
+        s[m].z *= a;
+        s[m].w *= a;
+      }
+    }
+
+    float4 u = {0.f, 0.f, 0.f, 0.f}, w = {0.f, 0.f, 0.f, 0.f};
+    float kq = 0.f;
+#pragma unroll
+    for (int m = 0; m < RPL; ++m) {
+      u.x = fmaf(s[m].x, kf[m], u.x);
+      u.y = fmaf(s[m].y, kf[m], u.y);
+      u.z = fmaf(s[m].z, kf[m], u.z);
+      u.w = fmaf(s[m].w, kf[m], u.w);
+      w.x = fmaf(s[m].x, qf[m], w.x);
+      w.y = fmaf(s[m].y, qf[m], w.y);
+      w.z = fmaf(s[m].z, qf[m], w.z);
+      w.w = fmaf(s[m].w, qf[m], w.w);
+      kq = fmaf(kf[m], qf[m], kq);
+    }
+    u.x = reduce_r8(u.x);
+    u.y = reduce_r8(u.y);
+    u.z = reduce_r8(u.z);
+    u.w = reduce_r8(u.w);
+    w.x = reduce_r8(w.x);
+    w.y = reduce_r8(w.y);
+    w.z = reduce_r8(w.z);
+    w.w = reduce_r8(w.w);
+    kq = reduce_r8(kq);
+
+    float4 d;
+    d.x = beta * (bf16_lo(cur.v.x) - u.x);
+    d.y = beta * (bf16_hi(cur.v.x) - u.y);
+    d.z = beta * (bf16_lo(cur.v.y) - u.z);
+    d.w = beta * (bf16_hi(cur.v.y) - u.w);
+#pragma unroll
+    for (int m = 0; m < RPL; ++m) {
+      s[m].x = fmaf(kf[m], d.x, s[m].x);
+      s[m].y = fmaf(kf[m], d.y, s[m].y);
+      s[m].z = fmaf(kf[m], d.z, s[m].z);
+      s[m].w = fmaf(kf[m], d.w, s[m].w);
+    }
+    if (!MULTI || t + 1 == p.n_commit) {
+#pragma unroll
+      for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
+    }
+    if (r8 == 0) {
+      float4 o;
+      o.x = p.scale * fmaf(kq, d.x, w.x);
+      o.y = p.scale * fmaf(kq, d.y, w.y);
+      o.z = p.scale * fmaf(kq, d.z, w.z);
+      o.w = p.scale * fmaf(kq, d.w, w.w);
+      *reinterpret_cast<float4*>(p.out + (bt * p.H + h) * DV + col0) = o;
+    }
+    if constexpr (MULTI) cur = nxt;
+  }
+}
+
+}  // namespace

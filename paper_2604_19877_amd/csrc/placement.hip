@@ -1,14 +1,17 @@
-// Per-request placement dispatch over a stack of mixer layers (host logic only).
+// Per-request placement dispatch over a stack of mixer layers (host logic; the fused kernel is in layer_fused.hip).
 //
 // Section 6 of the paper ("Per-request placement switching") lets every request name a placement,
 // i.e. one mixer per layer, and dispatches inside the layer on that name with no global mutable
 // state; its scheduler still batches same-placement requests together.  Here a batch may mix
 // placements freely: a plan groups the requests per (layer, mixer) once, and every kernel takes
-// the group's request list as an indirection, so a layer costs one launch per mixer present.
+// the group's request list as an indirection.  A one-token decode step at 128x128 states runs every layer
+// that mixes mixers as one fused launch (plus one merge launch); a layer with a single mixer present, and any
+// multi-token step, runs the stand-alone kernel of each mixer present.
 #include <cstring>
 #include <vector>
 
 #include "common.h"
+#include "layer_fused.h"
 
 struct sa_plan {
   int L = 0, B = 0;
@@ -90,13 +93,22 @@ extern "C" int placement_plan_count(const sa_plan* plan, int layer, char mixer) 
   return plan->counts[layer * 4 + mixer_index(mixer)];
 }
 
+namespace {
+
+size_t align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
+
+}  // namespace
+
+// Full attention's partial results sit at the start of the workspace, the sliding window's behind them (a fused
+// layer launch has both in flight at once).
 extern "C" size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* sh, int T, int max_seq_len, int window) {
   if (!plan || !sh) return 0;
   size_t need = 0;
   for (int l = 0; l < plan->L; ++l) {
     const int nf = plan->counts[l * 4 + 0], ns = plan->counts[l * 4 + 1];
-    if (nf) need = std::max(need, attn_decode_workspace_bytes(nf, T, sh->Hq, sh->Hkv, sh->D, max_seq_len, 0));
-    if (ns) need = std::max(need, attn_decode_workspace_bytes(ns, T, sh->Hq, sh->Hkv, sh->D, max_seq_len, window));
+    const size_t wf = nf ? attn_decode_workspace_bytes(nf, T, sh->Hq, sh->Hkv, sh->D, max_seq_len, 0) : 0;
+    const size_t ws = ns ? attn_decode_workspace_bytes(ns, T, sh->Hq, sh->Hkv, sh->D, max_seq_len, window) : 0;
+    need = std::max(need, align_up(wf, 256) + ws);
   }
   return need;
 }
@@ -110,25 +122,60 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
   SA_REQUIRE(static_cast<long long>(sh->H) * sh->dv == static_cast<long long>(sh->Hq) * sh->D, SA_EINVAL,
              "%s: H*dv must equal Hq*D so that all mixers share the output rows", name);
   const int B = plan->B;
+  const bool can_fuse = T == 1 && sh->dk == 128 && sh->dv == 128 && sh->Hkv >= 1 && sh->Hq / sh->Hkv <= 16;
   // Two passes over the stack: the first only checks every launch's arguments, so that a bad descriptor
   // anywhere is reported before anything has been enqueued.
   for (int pass = 0; pass < 2; ++pass) {
     const bool check = pass == 0;
     for (int l = 0; l < plan->L; ++l) {
       const sa_layer_io& x = io[l];
+      const int* cnt = &plan->counts[l * 4];
+      const int32_t* lists[4];
+      for (int m = 0; m < 4; ++m) lists[m] = plan->dev_lists + plan->offsets[l * 4 + m];
+      // where each attention kind keeps its partial results
+      const size_t need_fa = cnt[0] ? attn_decode_workspace_bytes(cnt[0], T, sh->Hq, sh->Hkv, sh->D, x.max_seq_len, 0) : 0;
+      const size_t off_swa = std::min(align_up(need_fa, 256), workspace_bytes);
+      char* ws_swa = workspace ? static_cast<char*>(workspace) + off_swa : nullptr;
+      const size_t ws_swa_bytes = workspace_bytes - off_swa;
+      const int present = (cnt[0] > 0) + (cnt[1] > 0) + (cnt[2] > 0) + (cnt[3] > 0);
+
+      if (can_fuse && present >= 2) {
+        sa::AttnLaunch fa, swa;
+        sa::DeltaLaunch kda, gdn;
+        fa.rows = swa.rows = kda.rows = gdn.rows = 0;
+        sa_status st = SA_OK;
+        if (cnt[0])
+          st = sa::attn_prepare(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, lists[0], cnt[0], x.out, B,
+                                T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, 0, attn_scale, workspace, workspace_bytes,
+                                &fa);
+        if (st == SA_OK && cnt[1])
+          st = sa::attn_prepare(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, lists[1], cnt[1], x.out, B,
+                                T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, window, attn_scale, ws_swa, ws_swa_bytes,
+                                &swa);
+        if (st == SA_OK && cnt[2])
+          st = sa::delta_prepare(true, x.q, x.k, x.v, x.alpha_vec, x.beta, x.state, x.state, x.out, x.slot_idx, lists[2], cnt[2], B, T,
+                                 sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, &kda);
+        if (st == SA_OK && cnt[3])
+          st = sa::delta_prepare(false, x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, lists[3], cnt[3], B,
+                                 T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, &gdn);
+        if (st == SA_OK && !check) st = sa::layer_fused_launch(fa, swa, kda, gdn, stream);
+        if (st != SA_OK) return st;
+        continue;
+      }
+
       for (int m = 0; m < 4; ++m) {
-        const int n = plan->counts[l * 4 + m];
+        const int n = cnt[m];
         if (n == 0) continue;
-        const int32_t* list = plan->dev_lists + plan->offsets[l * 4 + m];
+        const int32_t* list = lists[m];
         sa_status st;
         if (m == 0 || m == 1) {
           const int w = m == 0 ? 0 : window;
+          void* ws = m == 0 ? workspace : ws_swa;
+          const size_t ws_bytes = m == 0 ? workspace_bytes : ws_swa_bytes;
           st = check ? sa::check_attn_decode(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, list, n,
-                                             x.out, B, T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, w, workspace,
-                                             workspace_bytes)
+                                             x.out, B, T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, w, ws, ws_bytes)
                      : attn_decode(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, list, n, x.out, B,
-                                   T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, w, attn_scale, workspace,
-                                   workspace_bytes, stream);
+                                   T, sh->Hq, sh->Hkv, sh->D, sh->page_size, x.max_seq_len, w, attn_scale, ws, ws_bytes, stream);
         } else {
           const bool kda = m == 2;
           const float* alpha = kda ? x.alpha_vec : x.alpha_scalar;

@@ -15,9 +15,9 @@ pytestmark = pytest.mark.gpu
 H, DK, DV, HQ, HKV, D = 32, 128, 128, 32, 8, 128
 
 
-def build_stack(seed, L, B, T, ctx, max_pages):
+def build_stack(seed, L, B, T, ctx, max_pages, lens=None):
     """Host-side operands of every layer for the whole batch (each layer has its own)."""
-    lens = np.full(B, ctx, dtype=np.int32)
+    lens = np.full(B, ctx, dtype=np.int32) if lens is None else np.asarray(lens, dtype=np.int32)
     layers = []
     for l in range(L):
         r = gen.recurrent_inputs(seed + 10 * l, B, T, H, H, DK, DV, False)
@@ -79,6 +79,49 @@ def test_48_layer_stack_three_placements(T):
                 assert rel_err(got_s[r], ref_states[l][r]) <= STATE_TOL, (l, r, m)
             else:
                 assert np.array_equal(got_s[r], layers[l]["state"][r]), (l, r, m)   # attention rows leave the state alone
+
+
+def test_all_four_mixers_in_every_layer_ragged_and_empty_contexts():
+    """Four placements rotated against each other: every layer runs all four mixers in one fused launch, over
+    contexts of very different lengths (one empty, one of a single token, one ending mid-page)."""
+    L, B, ctx, window, max_pages = 8, 9, 1500, 200, 96
+    placements = ["FSKGFSKG", "SKGFSKGF", "KGFSKGFS", "GFSKGFSK"]
+    pid = np.array([0, 1, 2, 3, 3, 2, 1, 0, 2], dtype=np.int32)
+    lens = [1500, 0, 1, 777, 16, 1203, 15, 450, 1499]
+    layers = build_stack(5300, L, B, 1, ctx, max_pages, lens)
+    plan = sa.placement_plan_create(placements, pid)
+    shapes = sa.sa_shapes(H, H, DK, DV, HQ, HKV, D, 16)
+    ws_bytes = sa.placement_workspace_bytes(plan, shapes, 1, ctx, window)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    keep, ios = [], []
+    for io in layers:
+        kphys, vphys = kl.to_physical(io["kpool"], io["vpool"])
+        t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
+        t["state"], t["kpool"], t["vpool"] = dev(io["state"].copy()), dev(kphys), dev(vphys)
+        t["out"] = torch.full((B, 1, H, DV), 55.0, dtype=torch.float32, device="cuda")
+        keep.append(t)
+        ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"], alpha_vec=t["alpha_vec"],
+                                    beta=t["beta"], state=t["state"], q_attn=t["qa"], kpool=t["kpool"], vpool=t["vpool"],
+                                    n_pages=io["n_pages"], page_table=t["page_table"], seq_lens=t["seq_lens"],
+                                    max_pages=max_pages, max_seq_len=ctx, out=t["out"]))
+    for l in range(L):
+        assert all(sa.placement_plan_count(plan, l, m) >= 2 for m in "FSKG")
+    sa.placement_decode(plan, ios, shapes, 1, window, D ** -0.5, DK ** -0.5, ws, ws_bytes)
+    torch.cuda.synchronize()
+    sa.placement_plan_destroy(plan)
+    ref_outs, ref_states = om.placement_decode(placements, pid, layers, window, D ** -0.5, DK ** -0.5)
+    for l in range(L):
+        got_o, got_s = host(keep[l]["out"]), host(keep[l]["state"])
+        for r in range(B):
+            m = placements[pid[r]][l]
+            if m in "FS" and lens[r] == 0:
+                assert not got_o[r].any(), (l, r)          # an empty context reads nothing and returns zeros
+                continue
+            assert rel_err(got_o[r], ref_outs[l][r]) <= OUT_TOL, (l, r, m)
+            if m in "KG":
+                assert rel_err(got_s[r], ref_states[l][r]) <= STATE_TOL, (l, r, m)
+            else:
+                assert np.array_equal(got_s[r], layers[l]["state"][r]), (l, r, m)
 
 
 def test_same_placement_for_all_requests_and_empty_batch():
