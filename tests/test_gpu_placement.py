@@ -124,6 +124,70 @@ def test_all_four_mixers_in_every_layer_ragged_and_empty_contexts():
                 assert np.array_equal(got_s[r], layers[l]["state"][r]), (l, r, m)
 
 
+def run_stack(placements, pid, layers, T, window, ctx, max_pages, slot=None, n_slots=None):
+    """One placement_decode step over host-side layers; returns the outputs and states as numpy arrays."""
+    B = len(pid)
+    plan = sa.placement_plan_create(placements, pid)
+    try:
+        shapes = sa.sa_shapes(H, H, DK, DV, HQ, HKV, D, 16)
+        ws_bytes = sa.placement_workspace_bytes(plan, shapes, T, ctx, window)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+        keep, ios = [], []
+        for io in layers:
+            kphys, vphys = kl.to_physical(io["kpool"], io["vpool"])
+            t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
+            state = io["state"].copy()
+            if slot is not None:                      # states live in a larger slot array, addressed through slot_idx
+                pool = np.full((n_slots,) + state.shape[1:], 9.0, dtype=np.float32)
+                pool[slot] = state
+                state = pool
+            t["state"], t["kpool"], t["vpool"] = dev(state), dev(kphys), dev(vphys)
+            t["slot"] = dev(slot) if slot is not None else None
+            t["out"] = torch.full((B, T, H, DV), 55.0, dtype=torch.float32, device="cuda")
+            keep.append(t)
+            ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"], alpha_vec=t["alpha_vec"],
+                                        beta=t["beta"], state=t["state"], slot_idx=t["slot"], q_attn=t["qa"], kpool=t["kpool"],
+                                        vpool=t["vpool"], n_pages=io["n_pages"], page_table=t["page_table"],
+                                        seq_lens=t["seq_lens"], max_pages=max_pages, max_seq_len=ctx, out=t["out"]))
+        sa.placement_decode(plan, ios, shapes, T, window, D ** -0.5, DK ** -0.5, ws, ws_bytes)
+        torch.cuda.synchronize()
+    finally:
+        sa.placement_plan_destroy(plan)
+    return [host(t["out"]) for t in keep], [host(t["state"]) for t in keep]
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_random_stacks(case):
+    """Seeded random stacks: number of layers, batch, placements, mixers per layer, ragged lengths, window, token
+    count and state slots all vary, so layers with one, two, three and four mixers present all occur."""
+    rng = np.random.default_rng(9700 + case)
+    L, B = int(rng.integers(2, 7)), int(rng.integers(1, 11))
+    n_pl = int(rng.integers(1, 5))
+    T = int(rng.choice([1, 1, 1, 2, 4]))
+    placements = ["".join(rng.choice(list("FSKG"), size=L)) for _ in range(n_pl)]
+    pid = rng.integers(0, n_pl, size=B).astype(np.int32)
+    ctx = int(rng.choice([96, 700, 2100]))
+    max_pages = (ctx + 15) // 16 + int(rng.integers(0, 3))
+    lens = rng.integers(T, ctx + 1, size=B).astype(np.int32)
+    lens[rng.integers(B)] = ctx
+    window = int(rng.choice([16, 100, 512, 5000]))
+    n_slots = B + int(rng.integers(0, 3))
+    slot = rng.permutation(n_slots)[:B].astype(np.int32)
+    layers = build_stack(9800 + 100 * case, L, B, T, ctx, max_pages, lens)
+    outs, states = run_stack(placements, pid, layers, T, window, ctx, max_pages, slot, n_slots)
+    ref_outs, ref_states = om.placement_decode(placements, pid, layers, window, D ** -0.5, DK ** -0.5)
+    for l in range(L):
+        for r in range(B):
+            m = placements[pid[r]][l]
+            assert rel_err(outs[l][r], ref_outs[l][r]) <= OUT_TOL, (case, l, r, m)
+            if m in "KG":
+                assert rel_err(states[l][slot[r]], ref_states[l][r]) <= STATE_TOL, (case, l, r, m)
+            else:
+                assert np.array_equal(states[l][slot[r]], layers[l]["state"][r]), (case, l, r, m)
+        unused = [x for x in range(n_slots) if x not in slot]
+        assert (states[l][unused] == 9.0).all()
+
+
 def test_same_placement_for_all_requests_and_empty_batch():
     """All requests on one placement: every layer is a single launch over the whole batch."""
     L, B, ctx, window, max_pages = 4, 3, 200, 64, 16
