@@ -239,10 +239,16 @@ sa_status placement_plan_create(const char* const* placements, int n_placements,
 void placement_plan_destroy(sa_plan* plan);
 /* Number of requests that run mixer `mixer` ('F','S','K','G') at layer `layer`; -1 on bad arguments. */
 int placement_plan_count(const sa_plan* plan, int layer, char mixer);
+/* Bytes of device workspace placement_decode needs for this plan (0 if no layer splits its contexts into page
+ * ranges): the largest sum over a layer of its full-attention and its sliding-window partial results, which a
+ * fused layer launch keeps side by side. */
 size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, int T, int max_seq_len, int window);
 /* io: host array of L descriptors.  Checks the arguments of every launch of the stack first (nothing is
- * enqueued if any is bad), then enqueues, layer by layer, one launch per mixer present in that layer over
- * that mixer's request list.  Recurrent layers commit all T steps in place. */
+ * enqueued if any is bad), then enqueues layer by layer.  A one-token step (T == 1) at 128x128 states runs a layer
+ * in which two or more mixers are present as one fused launch over all their request lists, followed by one merge
+ * launch if an attention call has several page ranges; any other layer or step runs one launch (attention: plus a
+ * merge) per mixer present.  Results do not depend on which of the two is taken.  Recurrent layers commit all T
+ * steps in place. */
 sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,
                            float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes, void* stream);
 
