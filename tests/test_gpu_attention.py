@@ -198,7 +198,7 @@ def test_full_size_batch64_sampled_rows(mode):
     got = gpu_attention(q, kp, vp, table, lens, 1, window, max_len, n_pages=n_pages)
     assert np.isfinite(got).all()
     rng = np.random.default_rng(9)
-    samples = [(int(rng.integers(B)), int(rng.integers(HQ))) for _ in range(6)] + [(0, 0), (B - 1, HQ - 1)]
+    samples = [(int(rng.integers(B)), int(rng.integers(HQ))) for _ in range(22)] + [(0, 0), (B - 1, HQ - 1)]
     _check_sampled_rows(got, q, kp, vp, table, lens, window, samples)
 
 

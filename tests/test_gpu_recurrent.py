@@ -68,7 +68,7 @@ def test_full_shape_256_steps_sampled_tiles(kda, B):
     o, S = run_gpu(kda, p, S0, B, 1, H, H, dk, dv, scale)
     assert np.isfinite(o).all() and np.isfinite(S).all()
     rng = np.random.default_rng(5)
-    tiles = [(int(rng.integers(B)), int(rng.integers(H))) for _ in range(48)] + [(0, 0), (B - 1, H - 1)]
+    tiles = [(int(rng.integers(B)), int(rng.integers(H))) for _ in range(254)] + [(0, 0), (B - 1, H - 1)]
     seq = {n: as_sequence(p, n) for n in p}
     for (b, h) in tiles:
         sl = (slice(b, b + 1), slice(None), slice(h, h + 1))
