@@ -73,6 +73,20 @@ sa_status kda_decode_step(const void* q, const void* k, const void* v, const flo
                           const float* state_in, float* state_out, float* out,
                           const int32_t* slot_idx, const int32_t* req_idx, int n_req,
                           int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream);
+/* The same steps with the committed prefix chosen per request (Appendix "Speculative Decoding": every request of a
+ * batch accepts its own number of drafted tokens): n_commit_rows is a device array int32 [B], indexed by batch row
+ * like q; row b's state_out tile receives the state after n_commit_rows[b] steps, values outside [0,T] are clamped
+ * to that range.  Everything else as above; SA_EINVAL if n_commit_rows is NULL or not 4-byte aligned. */
+sa_status gdn_decode_step_var(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                              const float* state_in, float* state_out, float* out,
+                              const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                              int B, int T, int H, int Hk, int dk, int dv, float scale,
+                              const int32_t* n_commit_rows, void* stream);
+sa_status kda_decode_step_var(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                              const float* state_in, float* state_out, float* out,
+                              const int32_t* slot_idx, const int32_t* req_idx, int n_req,
+                              int B, int T, int H, int Hk, int dk, int dv, float scale,
+                              const int32_t* n_commit_rows, void* stream);
 
 /* State tiles.  A recurrent state is dk*dv fp32 values per (slot, head); callers that do not want to depend on the
  * order inside a tile convert with these (Appendix B: "a state matrix S in R^{dk x dv}" per head).  In this library a

@@ -48,11 +48,14 @@ class sa_block_io(ctypes.Structure):
 
 _BLOCK_ARGS = [ctypes.POINTER(sa_block_io)] + [c_void_p] * 5 + [c_int] * 6 + [c_float, c_void_p]
 _RECURRENT_ARGS = [c_void_p] * 10 + [c_int] * 7 + [c_float, c_int, c_void_p]
+_RECURRENT_VAR_ARGS = [c_void_p] * 10 + [c_int] * 7 + [c_float, c_void_p, c_void_p]
 _SIGNATURES = {
     "sa_last_error": (c_char_p, []),
     "sa_version": (c_int, []),
     "gdn_decode_step": (c_int, _RECURRENT_ARGS),
     "kda_decode_step": (c_int, _RECURRENT_ARGS),
+    "gdn_decode_step_var": (c_int, _RECURRENT_VAR_ARGS),
+    "kda_decode_step_var": (c_int, _RECURRENT_VAR_ARGS),
     "gdn_chunk_steps": (c_int, _RECURRENT_ARGS),
     "kda_chunk_steps": (c_int, _RECURRENT_ARGS),
     "gdn_block_decode": (c_int, _BLOCK_ARGS),
@@ -156,6 +159,20 @@ def kda_decode_step(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, re
                     n_commit, stream=None):
     _recurrent(lib().kda_decode_step, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
                Hk, dk, dv, scale, n_commit, stream)
+
+
+def gdn_decode_step_var(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,
+                        n_commit_rows, stream=None):
+    _check(lib().gdn_decode_step_var(_ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), _ptr(state_in), _ptr(state_out),
+                                     _ptr(out), _ptr(slot_idx), _ptr(req_idx), n_req, B, T, H, Hk, dk, dv, scale,
+                                     _ptr(n_commit_rows), _stream(stream)))
+
+
+def kda_decode_step_var(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,
+                        n_commit_rows, stream=None):
+    _check(lib().kda_decode_step_var(_ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(beta), _ptr(state_in), _ptr(state_out),
+                                     _ptr(out), _ptr(slot_idx), _ptr(req_idx), n_req, B, T, H, Hk, dk, dv, scale,
+                                     _ptr(n_commit_rows), _stream(stream)))
 
 
 def gdn_chunk_steps(q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv, scale,

@@ -50,7 +50,7 @@ sa_status check_attn_decode(const void* q, const void* kpool, const void* vpool,
 sa_status chunked_steps(bool kda, bool dry_run, const char* name, const void* q, const void* k, const void* v, const float* alpha,
                         const float* beta, const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
                         const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit,
-                        void* stream);
+                        const int32_t* n_commit_rows, void* stream);
 
 // Turns the sticky launch error (if any) into a status.
 sa_status check_launch(const char* what);

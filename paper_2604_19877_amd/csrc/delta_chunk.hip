@@ -57,6 +57,7 @@ struct ChunkParams {
   int T, H, Hk;
   float scale;
   int n_commit;  // state_out receives the state after this many tokens (0 .. T)
+  const int32_t* n_commit_rows;  // optional, device int32[B]: that count per request (clamped to [0,T]); overrides n_commit
 };
 
 constexpr int kD = 128;          // dk = dv
@@ -210,6 +211,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
   // Both indices are the same for the whole workgroup; saying so keeps every base address in scalar registers.
   const int b = __builtin_amdgcn_readfirstlane(p.req_idx ? p.req_idx[r] : r);
   const int slot = __builtin_amdgcn_readfirstlane(p.slot_idx ? p.slot_idx[b] : b);
+  const int n_commit = __builtin_amdgcn_readfirstlane(p.n_commit_rows ? min(max(p.n_commit_rows[b], 0), p.T) : p.n_commit);
   const int hk = h / (p.H / p.Hk);
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -245,8 +247,8 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
   const int n_chunks = (p.T + kC - 1) / kC;
   for (int ch = 0; ch < n_chunks; ++ch) {
     const int t0 = ch * kC;
-    const int n_keep = p.n_commit - t0;  // tokens of this chunk that the stored state includes, if it is stored here
-    if (n_keep == 0 && p.n_commit < p.T && (t0 > 0 || sout != sin)) store_tile(S, sout, lane_off);
+    const int n_keep = n_commit - t0;  // tokens of this chunk that the stored state includes, if it is stored here
+    if (n_keep == 0 && n_commit < p.T && (t0 > 0 || sout != sin)) store_tile(S, sout, lane_off);
     unsigned char* const stage = lds + (ch & 1) * kStageB;
     unsigned char* const k_tok = stage;                       // [16 tokens][kTokRowB]
     unsigned char* const q_tok = stage + kC * kTokRowB;
@@ -350,7 +352,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
 
     // The stored state ends inside this chunk (a verify pass whose later tokens may be rejected): the same
     // update with the decay taken up to token n_keep-1 and the later tokens left out, written straight to memory.
-    if (n_keep > 0 && n_keep < kC && p.n_commit < p.T) {
+    if (n_keep > 0 && n_keep < kC && n_commit < p.T) {
       uint32_t keep_off = lane_off;
       asm volatile("" : "+v"(keep_off));
       const float log_keep = __shfl(log_sum, n_keep - 1);
@@ -412,7 +414,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     // The per-wavefront matrices are rewritten in the next chunk only after this chunk's reads (program order).
   }
 
-  if (p.n_commit == p.T) store_tile(S, sout, lane_off);
+  if (n_commit == p.T) store_tile(S, sout, lane_off);
 }
 
 
@@ -490,6 +492,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
   // Both indices are the same for the whole workgroup; saying so keeps every base address in scalar registers.
   const int b = __builtin_amdgcn_readfirstlane(p.req_idx ? p.req_idx[r] : r);
   const int slot = __builtin_amdgcn_readfirstlane(p.slot_idx ? p.slot_idx[b] : b);
+  const int n_commit = __builtin_amdgcn_readfirstlane(p.n_commit_rows ? min(max(p.n_commit_rows[b], 0), p.T) : p.n_commit);
   const int hk = h / (p.H / p.Hk);
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -534,7 +537,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
     }
   __builtin_amdgcn_sched_barrier(0);
 
-  if (p.n_commit == 0 && sout != sin) store_tile(S, sout, lane_off);
+  if (n_commit == 0 && sout != sin) store_tile(S, sout, lane_off);
   const int n_chunks = (p.T + kC - 1) / kC;
   for (int ch = 0; ch < n_chunks; ++ch) {
     const int t0 = ch * kC;
@@ -560,7 +563,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
       int stop = __builtin_amdgcn_readfirstlane(min(limit[0], limit[1]));  // the same for all lanes
       // A pass never straddles the token after which the state is stored: that state is then simply the tile
       // as it stands after the pass.
-      const int n_keep = p.n_commit - t0;
+      const int n_keep = n_commit - t0;
       if (first < n_keep && n_keep < stop) stop = n_keep;
 
       // (2) Operands of this pass from the raw token this thread fetched.
@@ -708,12 +711,12 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
         }
       }
       first = stop;
-      if (t0 + first == p.n_commit && p.n_commit < p.T) store_tile(S, sout, lane_off);  // first > 0 here
+      if (t0 + first == n_commit && n_commit < p.T) store_tile(S, sout, lane_off);  // first > 0 here
     }
     cur = nxt;
   }
 
-  if (p.n_commit == p.T) store_tile(S, sout, lane_off);
+  if (n_commit == p.T) store_tile(S, sout, lane_off);
 }
 
 }  // namespace
@@ -724,7 +727,7 @@ template <bool KDA>
 sa_status chunk_launch(bool dry_run, const char* name, const void* q, const void* k, const void* v, const float* alpha,
                        const float* beta, const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
                        const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit,
-                       void* stream) {
+                       const int32_t* n_commit_rows, void* stream) {
   SA_REQUIRE(B >= 0 && T >= 1, SA_EINVAL, "%s: need B >= 0 and T >= 1 (B=%d, T=%d)", name, B, T);
   SA_REQUIRE(H >= 1 && Hk >= 1 && H % Hk == 0, SA_EINVAL, "%s: H must be a positive multiple of Hk (H=%d, Hk=%d)", name, H, Hk);
   SA_REQUIRE(n_commit >= 0 && n_commit <= T, SA_EINVAL, "%s: n_commit=%d outside [0,T=%d]", name, n_commit, T);
@@ -735,13 +738,13 @@ sa_status chunk_launch(bool dry_run, const char* name, const void* q, const void
   SA_REQUIRE(q && k && v && alpha && beta && state_in && state_out && out, SA_EINVAL, "%s: null pointer", name);
   SA_REQUIRE(sa::aligned(q, 16) && sa::aligned(k, 16) && sa::aligned(v, 16) && sa::aligned(state_in, 16) &&
                  sa::aligned(state_out, 16) && sa::aligned(out, 16) && sa::aligned(alpha, KDA ? 16 : 4) && sa::aligned(beta, 4) &&
-                 sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4),
+                 sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4) && sa::aligned(n_commit_rows, 4),
              SA_EINVAL, "%s: misaligned pointer", name);
   SA_REQUIRE(static_cast<long long>(rows) * H <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many tiles", name);
   if (dry_run) return SA_OK;
 
   ChunkParams p{static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
-                alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale, n_commit};
+                alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale, n_commit, n_commit_rows};
   const dim3 grid(static_cast<unsigned>(rows * H));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (KDA) {
@@ -758,12 +761,12 @@ sa_status chunk_launch(bool dry_run, const char* name, const void* q, const void
 sa_status sa::chunked_steps(bool kda, bool dry_run, const char* name, const void* q, const void* k, const void* v,
                             const float* alpha, const float* beta, const float* state_in, float* state_out, float* out,
                             const int32_t* slot_idx, const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
-                            float scale, int n_commit, void* stream) {
+                            float scale, int n_commit, const int32_t* n_commit_rows, void* stream) {
   if (kda)
     return chunk_launch<true>(dry_run, name, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk,
-                              dk, dv, scale, n_commit, stream);
+                              dk, dv, scale, n_commit, n_commit_rows, stream);
   return chunk_launch<false>(dry_run, name, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk,
-                             dk, dv, scale, n_commit, stream);
+                             dk, dv, scale, n_commit, n_commit_rows, stream);
 }
 
 extern "C" sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
@@ -771,7 +774,7 @@ extern "C" sa_status gdn_chunk_steps(const void* q, const void* k, const void* v
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
                                      float scale, int n_commit, void* stream) {
   return chunk_launch<false>(false, "gdn_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B,
-                             T, H, Hk, dk, dv, scale, n_commit, stream);
+                             T, H, Hk, dk, dv, scale, n_commit, nullptr, stream);
 }
 
 extern "C" sa_status kda_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
@@ -779,5 +782,5 @@ extern "C" sa_status kda_chunk_steps(const void* q, const void* k, const void* v
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
                                      float scale, int n_commit, void* stream) {
   return chunk_launch<true>(false, "kda_chunk_steps", q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B,
-                            T, H, Hk, dk, dv, scale, n_commit, stream);
+                            T, H, Hk, dk, dv, scale, n_commit, nullptr, stream);
 }

@@ -30,7 +30,8 @@ constexpr int kChunkedFrom = 5;  // tokens per call from which the decode steps 
 // Checks the arguments of one recurrent step and, when they pass, describes its launch in *launch (if not null).
 sa_status sa::delta_prepare(bool kda, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                             const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
-                            int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, sa::DeltaLaunch* launch) {
+                            int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, const int32_t* n_commit_rows,
+                            sa::DeltaLaunch* launch) {
   const char* name = kda ? "kda_decode_step" : "gdn_decode_step";
   if (launch) {
     launch->rows = 0;
@@ -47,7 +48,7 @@ sa_status sa::delta_prepare(bool kda, const void* q, const void* k, const void* 
   SA_REQUIRE(q && k && v && alpha && beta && state_in && state_out && out, SA_EINVAL, "%s: null pointer", name);
   SA_REQUIRE(sa::aligned(q, 16) && sa::aligned(k, 16) && sa::aligned(v, 16) && sa::aligned(state_in, 16) &&
                  sa::aligned(state_out, 16) && sa::aligned(out, 16) && sa::aligned(alpha, kda ? 16 : 4) &&
-                 sa::aligned(beta, 4) && sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4),
+                 sa::aligned(beta, 4) && sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4) && sa::aligned(n_commit_rows, 4),
              SA_EINVAL, "%s: misaligned pointer", name);
   SA_REQUIRE(static_cast<long long>(rows) * H <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many tiles", name);
   // From 5 tokens per call the chunk-parallel kernels are faster at 128x128 (8 tokens: 56 / 62 us against
@@ -55,11 +56,11 @@ sa_status sa::delta_prepare(bool kda, const void* q, const void* k, const void* 
   if (dk == 128 && T >= kChunkedFrom) {
     if (launch) launch->chunked = true;
     return sa::chunked_steps(kda, true, name, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk,
-                             dv, scale, n_commit, nullptr);
+                             dv, scale, n_commit, n_commit_rows, nullptr);
   }
   if (!launch) return SA_OK;
   launch->p = DeltaParams{static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
-                          alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale, n_commit};
+                          alpha, beta, state_in, state_out, out, slot_idx, req_idx, T, H, Hk, scale, n_commit, n_commit_rows};
   launch->rows = rows;
   return SA_OK;
 }
@@ -69,21 +70,22 @@ namespace {
 template <bool KDA>
 sa_status step_launch(bool dry_run, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                       const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
-                      int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, void* stream) {
+                      int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, const int32_t* n_commit_rows,
+                      void* stream) {
   const char* name = KDA ? "kda_decode_step" : "gdn_decode_step";
   sa::DeltaLaunch l;
   sa_status st = sa::delta_prepare(KDA, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv,
-                                   scale, n_commit, &l);
+                                   scale, n_commit, n_commit_rows, &l);
   if (st != SA_OK || dry_run) return st;
   if (l.chunked)
     return sa::chunked_steps(KDA, false, name, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk,
-                             dv, scale, n_commit, stream);
+                             dv, scale, n_commit, n_commit_rows, stream);
   if (l.rows == 0) return SA_OK;
   const DeltaParams& p = l.p;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid(static_cast<unsigned>(l.rows * H));
   const int kid = KDA ? SA_K_KDA : SA_K_GDN;
-  const bool single = T == 1 && n_commit == 1;
+  const bool single = T == 1 && n_commit == 1 && !n_commit_rows;
   if (dk == 128 && single)
     sa::launch(kid, delta_step_kernel<128, 128, KDA, false>, grid, dim3(256), 0, s, p);
   else if (dk == 128)
@@ -102,7 +104,7 @@ extern "C" sa_status gdn_decode_step(const void* q, const void* k, const void* v
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
                                      float scale, int n_commit, void* stream) {
   return step_launch<false>(false, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B,
-                       T, H, Hk, dk, dv, scale, n_commit, stream);
+                       T, H, Hk, dk, dv, scale, n_commit, nullptr, stream);
 }
 
 extern "C" sa_status kda_decode_step(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
@@ -110,7 +112,7 @@ extern "C" sa_status kda_decode_step(const void* q, const void* k, const void* v
                                      const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
                                      float scale, int n_commit, void* stream) {
   return step_launch<true>(false, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T,
-                      H, Hk, dk, dv, scale, n_commit, stream);
+                      H, Hk, dk, dv, scale, n_commit, nullptr, stream);
 }
 
 // Argument check of a recurrent step without enqueueing anything (used by placement_decode to validate a
@@ -120,7 +122,27 @@ sa_status sa::check_recurrent_step(bool kda, const void* q, const void* k, const
                                    const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, int n_commit) {
   if (kda)
     return step_launch<true>(true, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
-                        Hk, dk, dv, 1.f, n_commit, nullptr);
+                        Hk, dk, dv, 1.f, n_commit, nullptr, nullptr);
   return step_launch<false>(true, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
-                       Hk, dk, dv, 1.f, n_commit, nullptr);
+                       Hk, dk, dv, 1.f, n_commit, nullptr, nullptr);
+}
+
+// The same steps with the committed prefix chosen per request (self-speculative decoding: every request accepts
+// its own number of drafted tokens).
+extern "C" sa_status gdn_decode_step_var(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                                         const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                                         const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
+                                         float scale, const int32_t* n_commit_rows, void* stream) {
+  SA_REQUIRE(n_commit_rows || B == 0, SA_EINVAL, "gdn_decode_step_var: n_commit_rows is null");
+  return step_launch<false>(false, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv,
+                            scale, 0, n_commit_rows, stream);
+}
+
+extern "C" sa_status kda_decode_step_var(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
+                                         const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
+                                         const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv,
+                                         float scale, const int32_t* n_commit_rows, void* stream) {
+  SA_REQUIRE(n_commit_rows || B == 0, SA_EINVAL, "kda_decode_step_var: n_commit_rows is null");
+  return step_launch<true>(false, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk, dv,
+                           scale, 0, n_commit_rows, stream);
 }

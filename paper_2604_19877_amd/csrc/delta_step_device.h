@@ -21,6 +21,7 @@ struct DeltaParams {
   int T, H, Hk;
   float scale;
   int n_commit;
+  const int32_t* n_commit_rows;  // optional, device int32[B]: the committed prefix of each request (clamped to [0,T]); overrides n_commit
 };
 
 // One prepared recurrent step: rows = request rows to launch over (0: nothing to do, or the call runs on the
@@ -35,7 +36,8 @@ struct DeltaLaunch {
 // delta_step.hip).
 sa_status delta_prepare(bool kda, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
                         const float* state_in, float* state_out, float* out, const int32_t* slot_idx, const int32_t* req_idx,
-                        int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, DeltaLaunch* launch);
+                        int n_req, int B, int T, int H, int Hk, int dk, int dv, float scale, int n_commit, const int32_t* n_commit_rows,
+                        DeltaLaunch* launch);
 
 }  // namespace sa
 
@@ -106,6 +108,9 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   const int row0 = r8 * RPL;
   const int col0 = wave * 32 + c8 * 4;
   const int T = MULTI ? p.T : 1;
+  // the same for the whole workgroup: kept in a scalar register
+  const int n_commit =
+      !MULTI ? 1 : __builtin_amdgcn_readfirstlane(p.n_commit_rows ? min(max(p.n_commit_rows[b], 0), T) : p.n_commit);
 
   const size_t tile = (static_cast<size_t>(slot) * p.H + h) * (DK * DV);
   const float* sin = p.state_in + tile + static_cast<size_t>(row0) * DV + col0;
@@ -123,7 +128,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + m * DV);
   __builtin_amdgcn_sched_barrier(0);
 
-  if (MULTI && p.n_commit == 0 && p.state_out != p.state_in) {
+  if (MULTI && n_commit == 0 && p.state_out != p.state_in) {
 #pragma unroll
     for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
   }
@@ -203,7 +208,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
       s[m].z = fmaf(kf[m], d.z, s[m].z);
       s[m].w = fmaf(kf[m], d.w, s[m].w);
     }
-    if (!MULTI || t + 1 == p.n_commit) {
+    if (!MULTI || t + 1 == n_commit) {
 #pragma unroll
       for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
     }

@@ -154,10 +154,10 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
                                 &swa);
         if (st == SA_OK && cnt[2])
           st = sa::delta_prepare(true, x.q, x.k, x.v, x.alpha_vec, x.beta, x.state, x.state, x.out, x.slot_idx, lists[2], cnt[2], B, T,
-                                 sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, &kda);
+                                 sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, nullptr, &kda);
         if (st == SA_OK && cnt[3])
           st = sa::delta_prepare(false, x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, lists[3], cnt[3], B,
-                                 T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, &gdn);
+                                 T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, nullptr, &gdn);
         if (st == SA_OK && !check) st = sa::layer_fused_launch(fa, swa, kda, gdn, stream);
         if (st != SA_OK) return st;
         continue;

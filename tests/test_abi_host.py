@@ -138,3 +138,21 @@ def test_stream_tiles_checks_its_arguments():
             sa.sa_stream_tiles(**a)
         assert e.value.status == sa.SA_EINVAL, bad
     sa.sa_stream_tiles(2, 16, 0, 0)   # no tiles: nothing to do, no error
+
+
+@pytest.mark.parametrize("fn", [sa.gdn_decode_step_var, sa.kda_decode_step_var])
+def test_per_request_commit_argument_errors(fn):
+    def call(**over):
+        a = dict(q=16, k=16, v=16, alpha=16, beta=16, state_in=16, state_out=16, out=16, slot_idx=None, req_idx=None,
+                 n_req=0, B=2, T=4, H=4, Hk=4, dk=128, dv=128, scale=1.0, n_commit_rows=16, stream=0)
+        a.update(over)
+        fn(**a)
+    for bad in (dict(n_commit_rows=None), dict(n_commit_rows=6), dict(T=0), dict(T=17), dict(Hk=3), dict(q=None)):
+        with pytest.raises(sa.SaError) as e:
+            call(**bad)
+        assert e.value.status == sa.SA_EINVAL, bad
+    with pytest.raises(sa.SaError) as e:
+        call(dk=96, dv=96)
+    assert e.value.status == sa.SA_EUNSUPPORTED
+    call(B=0, n_commit_rows=None)          # empty batch: nothing to do, no error
+    call(req_idx=16, n_req=0)              # empty request list

@@ -175,3 +175,38 @@ def test_stream_tiles_calibration_kernel_touches_exactly_its_tiles():
     assert torch.equal(tiles[:(n - 1) * 128 * 128], torch.full(((n - 1) * 128 * 128,), 0.01, device="cuda"))
     assert torch.equal(tiles[(n - 1) * 128 * 128:], before[guard + (n - 1) * 128 * 128:-guard] * 0.999)
     assert torch.equal(buf[:guard], before[:guard]) and torch.equal(buf[-guard:], before[-guard:])
+
+
+@pytest.mark.parametrize("kda", [False, True])
+@pytest.mark.parametrize("T,dk", [(4, 128), (8, 128), (13, 128), (3, 64), (1, 128)])
+def test_per_request_commit_counts(kda, T, dk):
+    """Every request commits its own number of drafted tokens in one call (T <= 4 on the register-resident kernel,
+    longer calls on the chunk-parallel one); counts outside [0, T] are clamped; unlisted rows stay untouched."""
+    B, H, Hk, dv = 7, 4, 2, dk
+    p = gen.recurrent_inputs(1600 + T + kda, B, T, H, Hk, dk, dv, kda)
+    S0 = gen.recurrent_state(1601, B * H, dk, dv, std=0.3).reshape(B, H, dk, dv)
+    counts = np.array([0, T, 1, T - 1, T + 5, -3, T // 2], dtype=np.int32)
+    req = np.array([6, 0, 1, 2, 3, 4], dtype=np.int32)            # row 5 is not processed
+    fn, ref_fn = (sa.kda_decode_step_var, om.kda_steps) if kda else (sa.gdn_decode_step_var, om.gdn_steps)
+    d = {n: dev(a) for n, a in p.items()}
+    for in_place in (False, True):
+        s_in = dev(S0.copy())
+        s_out = s_in if in_place else dev(np.full_like(S0, 3.0))
+        out = torch.full((B, T, H, dv), -7.0, dtype=torch.float32, device="cuda")
+        fn(d["q"], d["k"], d["v"], d["alpha"], d["beta"], s_in, s_out, out, None, dev(req), len(req), B, T, H, Hk, dk, dv, 0.4,
+           dev(counts))
+        torch.cuda.synchronize()
+        got_o, got_s = host(out), host(s_out)
+        for b in req:
+            n = int(min(max(counts[b], 0), T))
+            sl = slice(b, b + 1)
+            o_ref, S_ref = ref_fn(p["q"][sl], p["k"][sl], p["v"][sl], p["alpha"][sl], p["beta"][sl], S0[sl], 0.4, n_commit=n)
+            assert rel_err(got_o[b], o_ref[0]) <= OUT_TOL, (b, n)
+            if n == 0:
+                assert np.array_equal(got_s[b], S0[b]), b          # nothing committed: the tile is copied
+            else:
+                assert rel_err(got_s[b], S_ref[0]) <= STATE_TOL, (b, n)
+        assert (got_o[5] == -7.0).all()
+        assert np.array_equal(got_s[5], S0[5]) if in_place else (got_s[5] == 3.0).all()
+        if not in_place:
+            assert np.array_equal(host(s_in), S0)
