@@ -243,6 +243,9 @@ typedef struct {                 /* one per layer; every pointer is a device poi
   int max_pages;
   int max_seq_len;
   float* out;                    /* fp32 [B,T,H,dv] == [B,T,Hq,D] (needs H*dv == Hq*D) */
+  const int32_t* n_commit_rows;  /* recurrent: int32 [B], how many of the T steps each request's state keeps
+                                    (as in gdn_decode_step_var), or NULL = all T: a verify pass runs with zeros
+                                    and leaves the states alone, the pass after acceptance with the accepted counts */
 } sa_layer_io;
 
 /* placements: host array of n_placements strings, each of length L.  placement_id: host int32 [B],
@@ -261,8 +264,8 @@ size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, i
  * enqueued if any is bad), then enqueues layer by layer.  A one-token step (T == 1) at 128x128 states runs a layer
  * in which two or more mixers are present as one fused launch over all their request lists, followed by one merge
  * launch if an attention call has several page ranges; any other layer or step runs one launch (attention: plus a
- * merge) per mixer present.  Results do not depend on which of the two is taken.  Recurrent layers commit all T
- * steps in place. */
+ * merge) per mixer present.  Results do not depend on which of the two is taken.  Recurrent layers update their
+ * states in place, by all T steps or by each request's n_commit_rows. */
 sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,
                            float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes, void* stream);
 

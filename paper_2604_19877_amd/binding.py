@@ -35,7 +35,7 @@ class sa_layer_io(ctypes.Structure):
                 ("state", c_void_p), ("slot_idx", c_void_p),
                 ("q_attn", c_void_p), ("kpool", c_void_p), ("vpool", c_void_p), ("n_pages", c_int),
                 ("page_table", c_void_p), ("seq_lens", c_void_p), ("max_pages", c_int), ("max_seq_len", c_int),
-                ("out", c_void_p)]
+                ("out", c_void_p), ("n_commit_rows", c_void_p)]
 
 
 class sa_block_io(ctypes.Structure):

@@ -37,9 +37,6 @@ inline void launch(int kernel_id, K kernel, dim3 grid, dim3 block, unsigned lds_
 }
 
 // Argument checks of the hot entry points that enqueue nothing (same rules, same messages).
-sa_status check_recurrent_step(bool kda, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
-                               const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
-                               const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, int n_commit);
 sa_status check_attn_decode(const void* q, const void* kpool, const void* vpool, int n_pages, const int32_t* page_table,
                             int max_pages, const int32_t* seq_lens, const int32_t* req_idx, int n_req, float* out, int B, int T,
                             int Hq, int Hkv, int D, int page_size, int max_seq_len, int window, void* workspace,

@@ -115,18 +115,6 @@ extern "C" sa_status kda_decode_step(const void* q, const void* k, const void* v
                       H, Hk, dk, dv, scale, n_commit, nullptr, stream);
 }
 
-// Argument check of a recurrent step without enqueueing anything (used by placement_decode to validate a
-// whole stack before its first launch).
-sa_status sa::check_recurrent_step(bool kda, const void* q, const void* k, const void* v, const float* alpha, const float* beta,
-                                   const float* state_in, float* state_out, float* out, const int32_t* slot_idx,
-                                   const int32_t* req_idx, int n_req, int B, int T, int H, int Hk, int dk, int dv, int n_commit) {
-  if (kda)
-    return step_launch<true>(true, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
-                        Hk, dk, dv, 1.f, n_commit, nullptr, nullptr);
-  return step_launch<false>(true, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H,
-                       Hk, dk, dv, 1.f, n_commit, nullptr, nullptr);
-}
-
 // The same steps with the committed prefix chosen per request (self-speculative decoding: every request accepts
 // its own number of drafted tokens).
 extern "C" sa_status gdn_decode_step_var(const void* q, const void* k, const void* v, const float* alpha, const float* beta,

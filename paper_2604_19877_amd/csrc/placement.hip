@@ -139,7 +139,7 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
       const size_t ws_swa_bytes = workspace_bytes - off_swa;
       const int present = (cnt[0] > 0) + (cnt[1] > 0) + (cnt[2] > 0) + (cnt[3] > 0);
 
-      if (can_fuse && present >= 2) {
+      if (can_fuse && present >= 2 && !x.n_commit_rows) {
         sa::AttnLaunch fa, swa;
         sa::DeltaLaunch kda, gdn;
         fa.rows = swa.rows = kda.rows = gdn.rows = 0;
@@ -180,8 +180,14 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
           const bool kda = m == 2;
           const float* alpha = kda ? x.alpha_vec : x.alpha_scalar;
           if (check)
-            st = sa::check_recurrent_step(kda, x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T,
-                                          sh->H, sh->Hk, sh->dk, sh->dv, T);
+            st = sa::delta_prepare(kda, x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T, sh->H,
+                                   sh->Hk, sh->dk, sh->dv, rec_scale, T, x.n_commit_rows, nullptr);
+          else if (x.n_commit_rows && kda)
+            st = kda_decode_step_var(x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T, sh->H,
+                                     sh->Hk, sh->dk, sh->dv, rec_scale, x.n_commit_rows, stream);
+          else if (x.n_commit_rows)
+            st = gdn_decode_step_var(x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T, sh->H,
+                                     sh->Hk, sh->dk, sh->dv, rec_scale, x.n_commit_rows, stream);
           else if (kda)
             st = kda_decode_step(x.q, x.k, x.v, alpha, x.beta, x.state, x.state, x.out, x.slot_idx, list, n, B, T, sh->H, sh->Hk,
                                  sh->dk, sh->dv, rec_scale, T, stream);

@@ -124,7 +124,7 @@ def test_all_four_mixers_in_every_layer_ragged_and_empty_contexts():
                 assert np.array_equal(got_s[r], layers[l]["state"][r]), (l, r, m)
 
 
-def run_stack(placements, pid, layers, T, window, ctx, max_pages, slot=None, n_slots=None):
+def run_stack(placements, pid, layers, T, window, ctx, max_pages, slot=None, n_slots=None, n_commit_rows=None):
     """One placement_decode step over host-side layers; returns the outputs and states as numpy arrays."""
     B = len(pid)
     plan = sa.placement_plan_create(placements, pid)
@@ -143,17 +143,46 @@ def run_stack(placements, pid, layers, T, window, ctx, max_pages, slot=None, n_s
                 state = pool
             t["state"], t["kpool"], t["vpool"] = dev(state), dev(kphys), dev(vphys)
             t["slot"] = dev(slot) if slot is not None else None
+            t["commit"] = dev(n_commit_rows) if n_commit_rows is not None else None
             t["out"] = torch.full((B, T, H, DV), 55.0, dtype=torch.float32, device="cuda")
             keep.append(t)
             ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"], alpha_vec=t["alpha_vec"],
                                         beta=t["beta"], state=t["state"], slot_idx=t["slot"], q_attn=t["qa"], kpool=t["kpool"],
                                         vpool=t["vpool"], n_pages=io["n_pages"], page_table=t["page_table"],
-                                        seq_lens=t["seq_lens"], max_pages=max_pages, max_seq_len=ctx, out=t["out"]))
+                                        seq_lens=t["seq_lens"], max_pages=max_pages, max_seq_len=ctx, out=t["out"],
+                                        n_commit_rows=t["commit"]))
         sa.placement_decode(plan, ios, shapes, T, window, D ** -0.5, DK ** -0.5, ws, ws_bytes)
         torch.cuda.synchronize()
     finally:
         sa.placement_plan_destroy(plan)
     return [host(t["out"]) for t in keep], [host(t["state"]) for t in keep]
+
+
+@pytest.mark.parametrize("T", [1, 4, 8])
+def test_verify_pass_then_commit_of_accepted_prefixes(T):
+    """Self-speculative decoding over a stack: a verify pass scores T drafted tokens per request and leaves every
+    recurrent state alone (all counts zero); the second pass commits each request's own accepted prefix."""
+    L, B, ctx, window, max_pages = 6, 5, 300, 64, 20
+    placements = ["FKGSKG", "GGKFSK", "KSFGGF"]
+    pid = np.array([0, 1, 2, 0, 1], dtype=np.int32)
+    layers = build_stack(5400 + T, L, B, T, ctx, max_pages)
+    ref_outs, _ = om.placement_decode(placements, pid, layers, window, D ** -0.5, DK ** -0.5)
+    accepted = np.array([T, 0, T // 2, 1, max(T - 1, 0)], dtype=np.int32)
+    for counts in (np.zeros(B, dtype=np.int32), accepted):
+        outs, states = run_stack(placements, pid, layers, T, window, ctx, max_pages, n_commit_rows=counts)
+        for l in range(L):
+            for r in range(B):
+                m = placements[pid[r]][l]
+                assert rel_err(outs[l][r], ref_outs[l][r]) <= OUT_TOL, (l, r, m)       # all T read-outs either way
+                if m in "KG" and counts[r] > 0:
+                    fn = om.kda_steps if m == "K" else om.gdn_steps
+                    io, sl = layers[l], slice(r, r + 1)
+                    a = io["alpha_vec"] if m == "K" else io["alpha_scalar"]
+                    _, s_ref = fn(io["q"][sl], io["k"][sl], io["v"][sl], a[sl], io["beta"][sl], io["state"][sl], DK ** -0.5,
+                                  n_commit=int(counts[r]))
+                    assert rel_err(states[l][r], s_ref[0]) <= STATE_TOL, (l, r, m, int(counts[r]))
+                else:
+                    assert np.array_equal(states[l][r], layers[l]["state"][r]), (l, r, m)
 
 
 @pytest.mark.parametrize("case", range(8))
