@@ -242,10 +242,16 @@ def main():
 
 
 def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_pages, lens_fa, lens_swa, rec_scale,
-                attn_scale, stream, alg, reps=6):
+                attn_scale, stream, alg, reps=9):
     """Multi-token verify for self-speculative decoding: 4 and 8 drafted tokens per sequence scored in one pass
-    of each mixer at the batch-64 shapes (same state / KV bytes as a single-token step)."""
+    of each mixer at the batch-64 shapes (same state / KV bytes as a single-token step).  Median of the launches
+    after the first: the first launches of a kernel variant after a change of workload run several per cent slow."""
     res = {}
+
+    def median(ms):
+        tail = sorted(ms[1:])
+        return tail[len(tail) // 2]
+
     for T in (4, 8):
         for name, kda, fn, kids in (("gdn", False, sa.gdn_decode_step, (sa.SA_K_GDN, sa.SA_K_GDN_CHUNK)),
                                     ("kda", True, sa.kda_decode_step, (sa.SA_K_KDA, sa.SA_K_KDA_CHUNK))):
@@ -259,9 +265,9 @@ def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_
             torch.cuda.synchronize()
             sa.sa_prof_enable(False)
             ms = [t for kid in kids for t in sa.sa_prof_read(kid, reps)[2]]   # 5 tokens and more run on the chunk kernels
-            avg = sum(ms[1:]) / (len(ms) - 1)
+            avg = median(ms)
             nbytes = alg[name + "_decode_step"]
-            res["%s_T%d" % (name, T)] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
+            res["%s_T%d" % (name, T)] = {"median_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
                                          "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         q = dev(gen.attention_inputs(1910 + T, B, T, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"])
         ws_bytes = max(sa.attn_decode_workspace_bytes(B, T, HQ, HKV, D, CTX, 0),
@@ -277,9 +283,9 @@ def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_
             sa.sa_prof_enable(False)
             _, _, ms = sa.sa_prof_read(sa.SA_K_ATTN_SPLIT, reps)
             sa.sa_prof_read(sa.SA_K_ATTN_MERGE, reps)
-            avg = sum(ms[1:]) / (len(ms) - 1)
+            avg = median(ms)
             nbytes = alg["attn_split_" + name]
-            res["%s_T%d" % (name, T)] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
+            res["%s_T%d" % (name, T)] = {"median_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
                                          "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     return res
 
