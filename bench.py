@@ -224,6 +224,9 @@ def main():
         del kpool, vpool, rec
         torch.cuda.empty_cache()
         placement = placement_stack(torch, sa, stream)
+        torch.cuda.empty_cache()
+        scattered = placement_stack(torch, sa, stream, page_scatter="global")
+        placement["pages_shuffled_over_the_whole_pool"] = {k: scattered[k] for k in ("ms_per_step", "tokens_per_s", "frac_hbm_peak")}
         placement["launch_bound_case"] = small_stack_graph(torch)
 
     line = {
@@ -498,11 +501,11 @@ def preset_speedups(torch, gen, stream, batch=32, ctx=32768, steps=6):
                           "on 1xH100 at 32k; here only the token mixers run"}
 
 
-def placement_stack(torch, sa, stream, steps=8, warmup=2):
+def placement_stack(torch, sa, stream, steps=8, warmup=2, page_scatter="layer"):
     """One decode step of the 48-layer mixers-only stack at batch 128, 16384-token contexts, three
     placements of 12 FA / 12 SWA / 12 KDA / 12 GDN layers assigned per request."""
     from paper_2604_19877_amd.workloads import PlacementWorkload
-    w = PlacementWorkload(B=128, L=48, ctx=16384, window=WINDOW, T=1, seed=5000)
+    w = PlacementWorkload(B=128, L=48, ctx=16384, window=WINDOW, T=1, seed=5000, page_scatter=page_scatter)
     try:
         for _ in range(warmup):
             w.step(stream)
@@ -515,7 +518,9 @@ def placement_stack(torch, sa, stream, steps=8, warmup=2):
         nbytes = w.algorithmic_bytes()
         gbs = nbytes / (ms * 1e-3) / 1e9
         return {"workload": "48-layer mixers-only stack, batch 128, contexts 16384, 3 placements (12 FA/12 SWA/12 KDA/12 GDN "
-                            "each) assigned per request, one global paged KV pool, bounded SWA caches",
+                            "each) assigned per request, one global paged KV pool (%s), bounded SWA caches"
+                            % ("every layer's pages shuffled inside a region of its own" if page_scatter == "layer"
+                               else "all layers' pages shuffled over the whole pool"),
                 "ms_per_step": round(ms, 3), "tokens_per_s": round(w.B / (ms * 1e-3), 1), "steps": steps,
                 "alg_bytes": nbytes, "GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
                 "kv_pool_GiB": round(2 * w.n_pages * HKV * PAGE * D * 2 / 2 ** 30, 1)}

@@ -36,9 +36,15 @@ class PlacementWorkload:
     One global K pool and one global V pool serve every attention layer (per-layer page tables point
     into them); sliding-window layers map only the pages their window touches.  Recurrent layers hold
     state only for the requests that run a recurrent mixer there (slot maps).
+
+    page_scatter = "layer": every layer's cache is a region of its own in the pools (a serving engine allocates one
+    KV tensor per layer) and the pages of its requests are a seeded shuffle inside that region.  "global": the
+    pages of all layers are one seeded shuffle over the whole pools, which costs the attention kernels several per
+    cent at pools of 100 GiB (address translation reaches further).
     """
 
-    def __init__(self, B=128, L=48, ctx=16384, window=4096, T=1, seed=5000, n_placements=3, placements=None):
+    def __init__(self, B=128, L=48, ctx=16384, window=4096, T=1, seed=5000, n_placements=3, placements=None,
+                 page_scatter="layer"):
         import torch
         self.B, self.L, self.ctx, self.window, self.T = B, L, ctx, window, T
         if placements is None:
@@ -53,7 +59,17 @@ class PlacementWorkload:
         n_s = int((mixer == "S").sum())
         self.n_pages = n_f * self.max_pages + n_s * (self.max_pages - first_win) + 3
         rng = np.random.default_rng(seed)
-        perm = rng.permutation(self.n_pages).astype(np.int32)
+        if page_scatter == "global":
+            perm = rng.permutation(self.n_pages).astype(np.int32)
+        elif page_scatter == "layer":
+            perm, start = np.empty(self.n_pages, dtype=np.int32), 0
+            for l in range(L):
+                n = int((mixer[l] == "F").sum()) * self.max_pages + int((mixer[l] == "S").sum()) * (self.max_pages - first_win)
+                perm[start:start + n] = start + rng.permutation(n)
+                start += n
+            perm[start:] = np.arange(start, self.n_pages)          # the spare pages
+        else:
+            raise ValueError("page_scatter must be 'layer' or 'global'")
         g = torch.Generator(device="cuda")
         g.manual_seed(seed)
         self.kpool = torch.empty((self.n_pages, HKV, PAGE * D), dtype=torch.bfloat16, device="cuda")
