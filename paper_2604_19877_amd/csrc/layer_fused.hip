@@ -41,6 +41,21 @@ __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
   }
 }
 
+// A layer whose only mixers are the two recurrent ones: the same two tile bodies in one grid, without the
+// attention body's registers and LDS.
+struct RecurrentLayerParams {
+  sa::DeltaParams kda, gdn;
+  int end_kda;  // [0, end_kda) KDA tiles, the rest GDN tiles
+};
+
+__global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
+  const int id = blockIdx.x;
+  if (id < p.end_kda)
+    delta_step_body<128, 128, true, false>(p.kda, id);
+  else
+    delta_step_body<128, 128, false, false>(p.gdn, id - p.end_kda);
+}
+
 struct MergeParams {
   sa::AttnParams fa, swa;
   int end_fa;  // [0, end_fa) rows of the full-attention call, the rest of the sliding-window call
@@ -73,10 +88,18 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
   if (total == 0) return SA_OK;
   SA_REQUIRE((!fa.rows || fa.p.R <= 16) && (!swa.rows || swa.p.R <= 16), SA_EUNSUPPORTED, "%s: more than 16 query rows per KV head",
              name);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (n_fa + n_swa == 0) {
+    RecurrentLayerParams rp;
+    rp.kda = kda.p;
+    rp.gdn = gdn.p;
+    rp.end_kda = static_cast<int>(n_kda);
+    sa::launch(SA_K_LAYER, layer_recurrent_kernel, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, rp);
+    return sa::check_launch(name);
+  }
   p.end_fa = static_cast<int>(n_fa);
   p.end_swa = static_cast<int>(n_fa + n_swa);
   p.end_kda = static_cast<int>(n_fa + n_swa + n_kda);
-  hipStream_t s = static_cast<hipStream_t>(stream);
   sa::launch(SA_K_LAYER, layer_decode_kernel, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
   sa_status st = sa::check_launch(name);
   if (st != SA_OK) return st;

@@ -139,6 +139,8 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
       const size_t ws_swa_bytes = workspace_bytes - off_swa;
       const int present = (cnt[0] > 0) + (cnt[1] > 0) + (cnt[2] > 0) + (cnt[3] > 0);
 
+      // One fused launch when the layer mixes mixers (measured from batch 8 / 2048-token contexts to batch 128 /
+      // 16384: 26 % to 0 % faster than one launch per mixer).
       if (can_fuse && present >= 2 && !x.n_commit_rows) {
         sa::AttnLaunch fa, swa;
         sa::DeltaLaunch kda, gdn;
@@ -158,7 +160,8 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
         if (st == SA_OK && cnt[3])
           st = sa::delta_prepare(false, x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, lists[3], cnt[3], B,
                                  T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, nullptr, &gdn);
-        if (st == SA_OK && !check) st = sa::layer_fused_launch(fa, swa, kda, gdn, stream);
+        if (st != SA_OK) return st;
+        if (!check) st = sa::layer_fused_launch(fa, swa, kda, gdn, stream);
         if (st != SA_OK) return st;
         continue;
       }
