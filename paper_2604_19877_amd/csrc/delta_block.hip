@@ -69,8 +69,9 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
   __shared__ float sh_sumsq[WAVES], sh_osq[WAVES];
 
   const sa_block_io& io = p.io;
-  const int r = blockIdx.x / p.H;
-  const int h = blockIdx.x - r * p.H;
+  const int tile_id = interleaved_tile(blockIdx.x, gridDim.x);
+  const int r = tile_id / p.H;
+  const int h = tile_id - r * p.H;
   const int b = p.req_idx ? p.req_idx[r] : r;
   const int slot = p.slot_idx ? p.slot_idx[b] : b;
   const int group = p.H / p.Hk;

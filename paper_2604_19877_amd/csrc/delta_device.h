@@ -22,6 +22,13 @@ __device__ __forceinline__ void store_state(float* p, const float4& v) {
   __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
 }
 
+// Which tile the i-th of n workgroups visits.  Workgroups start in index order, so with the identity the ~1000
+// resident ones sweep one contiguous 64 MiB window of the states; visiting four quarters of the tile list in turn
+// keeps four windows a quarter of the list apart in flight, which the memory system serves faster once the list
+// spans 256 MiB and more (one GDN step, identity against this order: 128 MiB of states 47.5 / 47.5 us, 256 MiB
+// 95.2 / 92.3, 512 MiB 190.5 / 182.4, 1 GiB 390 / 366; two parts or eight are worse at some of these sizes).
+__device__ __forceinline__ int interleaved_tile(int i, int n) { return (n & 3) ? i : (i & 3) * (n >> 2) + (i >> 2); }
+
 // A per-(row, head) scalar read through the constant address space: the index is the same for the
 // whole workgroup, so this becomes a scalar-cache load instead of 64 identical vector loads.  The
 // gates are inputs and are not written while the kernel runs.
