@@ -19,7 +19,7 @@
 namespace {
 
 template <int DK, int DV, bool KDA, bool MULTI>
-__global__ __launch_bounds__(DV * 2, (KDA && MULTI && DV == 128) ? 3 : 1) void delta_step_kernel(DeltaParams p) {
+__global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
   delta_step_body<DK, DV, KDA, MULTI>(p, interleaved_tile(blockIdx.x, gridDim.x));
 }
 
