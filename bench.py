@@ -47,7 +47,7 @@ def parse_args():
                     help="only fit the per-mixer cost model 1/throughput = sum_m c_m n_m over 14 allocations of a 48-layer "
                          "stack (batch 32, 16384-token contexts) and print it")
     ap.add_argument("--preset-speedups", action="store_true",
-                    help="time the paper's recommended presets (layer counts per mixer) at 32768-token contexts and print "
+                    help="time the paper's recommended presets (layer counts per mixer) at 16384- and 32768-token contexts and print "
                          "their decode speedup over the all-FA preset, mixers only")
     ap.add_argument("--prefill", type=int, default=0, metavar="T",
                     help="only run the chunk-parallel recurrent kernels over T tokens per sequence (batch 64) and print their times")
@@ -460,45 +460,49 @@ def cost_table(np, torch, gen, stream, batch=32, ctx=16384, steps=6):
                                                  "note": "1xH100, whole 15B model incl. FFNs, vLLM, 16k, regression over 84 placements"}}
 
 
-def preset_speedups(torch, gen, stream, batch=32, ctx=32768, steps=6):
-    """Decode speedup of the paper's recommended presets over its all-FA preset at 32768-token contexts (Section 7,
-    "Placement Presets": layer counts per mixer and the speedup measured there), for the mixers alone on this GPU: all
-    requests share the preset, as in the paper's single-preset measurements; which layers get which mixer is a
-    seeded shuffle (time depends on the counts only)."""
+def preset_speedups(torch, gen, stream, batch=32, contexts=(16384, 32768), steps=6):
+    """Decode speedup of the paper's recommended presets over its all-FA preset at 16384- and 32768-token contexts
+    (Section 7, "Placement Presets": layer counts per mixer; the appendix table of full results: speedups at 16k and
+    32k), for the mixers alone on this GPU: all requests share the preset, as in the paper's single-preset
+    measurements; which layers get which mixer is a seeded shuffle (time depends on the counts only)."""
     from paper_2604_19877_amd.workloads import PlacementWorkload
-    presets = [("all-FA", (48, 0, 0, 0), 1.0), ("Reg|Lklhd-26", (12, 26, 6, 4), 2.9), ("Reg|Lklhd-18", (3, 25, 4, 16), 4.8),
-               ("Reg|Lklhd-13", (0, 16, 13, 19), 6.9), ("Reg|Lklhd-10", (0, 10, 5, 33), 10.7),
-               ("Idealized|All-18", (13, 32, 1, 2), 2.0), ("Idealized|Lklhd-6 / All-6", (0, 30, 5, 13), 6.2)]
-    rows = []
-    for i, (name, (f, s_, k, g_), paper) in enumerate(presets):
-        placement = gen.placement_string(6300 + i, 48, {"F": f, "S": s_, "K": k, "G": g_})
-        w = PlacementWorkload(B=batch, L=48, ctx=ctx, window=WINDOW, T=1, seed=6400 + i, placements=[placement])
-        try:
-            for _ in range(2):
-                w.step(stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(steps):
-                w.step(stream)
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3 / steps
-            nbytes = w.algorithmic_bytes()
-        finally:
-            w.close()
-        del w
-        torch.cuda.empty_cache()
-        rows.append({"preset": name, "layers_F_S_K_G": [f, s_, k, g_], "ms_per_step": round(ms, 3),
-                     "tokens_per_s": round(batch / (ms * 1e-3), 1), "alg_bytes": nbytes,
-                     "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "paper_speedup_context_only": paper})
-    base_ms, base_bytes = rows[0]["ms_per_step"], rows[0]["alg_bytes"]
-    for r in rows:
-        r["speedup_over_all_FA"] = round(base_ms / r["ms_per_step"], 2)
-        r["speedup_from_bytes_alone"] = round(base_bytes / r["alg_bytes"], 2)
-    return {"workload": "48-layer mixers-only stack, batch %d, contexts %d, w=%d, one preset per run" % (batch, ctx, WINDOW),
-            "presets": rows,
+    presets = [("all-FA", (48, 0, 0, 0), {16384: 1.0, 32768: 1.0}), ("Reg|Lklhd-26", (12, 26, 6, 4), {16384: 1.5, 32768: 2.85}),
+               ("Reg|Lklhd-18", (3, 25, 4, 16), {16384: 2.2, 32768: 4.76}), ("Reg|Lklhd-13", (0, 16, 13, 19), {16384: 2.7, 32768: 6.9}),
+               ("Reg|Lklhd-10", (0, 10, 5, 33), {16384: 4.2, 32768: 10.69}), ("Idealized|All-18", (13, 32, 1, 2), {16384: 1.1, 32768: 1.99}),
+               ("Idealized|Lklhd-6 / All-6", (0, 30, 5, 13), {16384: 2.4, 32768: 6.2})]
+    tables = []
+    for ctx in contexts:
+        rows = []
+        for i, (name, (f, s_, k, g_), paper) in enumerate(presets):
+            placement = gen.placement_string(6300 + i, 48, {"F": f, "S": s_, "K": k, "G": g_})
+            w = PlacementWorkload(B=batch, L=48, ctx=ctx, window=WINDOW, T=1, seed=6400 + i, placements=[placement])
+            try:
+                for _ in range(2):
+                    w.step(stream)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    w.step(stream)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) * 1e3 / steps
+                nbytes = w.algorithmic_bytes()
+            finally:
+                w.close()
+            del w
+            torch.cuda.empty_cache()
+            rows.append({"preset": name, "layers_F_S_K_G": [f, s_, k, g_], "ms_per_step": round(ms, 3),
+                         "tokens_per_s": round(batch / (ms * 1e-3), 1), "alg_bytes": nbytes,
+                         "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                         "paper_speedup_context_only": paper.get(ctx)})
+        base_ms, base_bytes = rows[0]["ms_per_step"], rows[0]["alg_bytes"]
+        for r in rows:
+            r["speedup_over_all_FA"] = round(base_ms / r["ms_per_step"], 2)
+            r["speedup_from_bytes_alone"] = round(base_bytes / r["alg_bytes"], 2)
+        tables.append({"workload": "48-layer mixers-only stack, batch %d, contexts %d, w=%d, one preset per run" % (batch, ctx, WINDOW),
+                       "context": ctx, "presets": rows})
+    return {"tables": tables,
             "paper_note": "the paper's speedups are decode throughput of the whole 15B model (FFNs, sampler, scheduler) under vLLM "
-                          "on 1xH100 at 32k; here only the token mixers run"}
+                          "on 1xH100; here only the token mixers run"}
 
 
 def placement_stack(torch, sa, stream, steps=8, warmup=2, page_scatter="layer"):
