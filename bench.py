@@ -388,6 +388,22 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
     nbytes = int(lens_swa_h.astype(np.int64).sum()) * 2 * HKV * D * 2
     res["fa_ragged_U8192_32768"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1),
                                     "alg_bytes": nbytes, "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    # the same full-attention step through a regular page table (every sequence's pages in a row): what a freshly filled
+    # cache looks like, and the pattern that concentrates on few memory channels unless workgroups are staggered
+    lens_full = torch.full((B,), CTX, dtype=torch.int32, device="cuda")
+    rows_table = torch.arange(B * max_pages, dtype=torch.int32, device="cuda").reshape(B, max_pages)
+    sa.sa_prof_enable(True)
+    for _ in range(reps):
+        sa.attn_decode(q, kpool, vpool, n_pages, rows_table, max_pages, lens_full, None, 0, out, B, 1, HQ, HKV, D, PAGE, CTX, 0,
+                       attn_scale, ws, ws_bytes, stream)
+    torch.cuda.synchronize()
+    sa.sa_prof_enable(False)
+    _, _, ms = sa.sa_prof_read(sa.SA_K_ATTN_SPLIT, reps)
+    sa.sa_prof_read(sa.SA_K_ATTN_MERGE, reps)
+    avg = sum(ms[2:]) / (len(ms) - 2)
+    nbytes = B * CTX * 2 * HKV * D * 2
+    res["fa_32768_pages_in_a_row"] = {"avg_us": round(avg * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1),
+                                      "alg_bytes": nbytes, "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     return res
 
 

@@ -157,9 +157,21 @@ __device__ __forceinline__ void attn_split_body(const AttnParams& p, const int g
   const int n_iter = first < pe ? (pe - first + kWaves - 1) / kWaves : 0;
 
   if (n_iter > 0) {
+    // The pages of the range are visited cyclically from a starting point that differs from workgroup to workgroup
+    // (the running softmax does not care about the order).  Workgroups start together and advance at the same pace;
+    // with a regular page table (pages of a request in a row, requests at a fixed distance) they would otherwise all
+    // be reading addresses a fixed multiple of the range length apart at any moment, which a few memory channels serve.
+    const uint32_t mix = static_cast<uint32_t>(r * p.nsplit + split) * 0x9E3779B1u;
+    const int rot = static_cast<int>((mix >> 8) % static_cast<uint32_t>(n_iter));
+    auto page_of = [&](int it) {
+      int pos = it + rot;
+      pos -= pos >= n_iter ? n_iter : 0;
+      return first + pos * kWaves;
+    };
     // Lane i of the wavefront keeps the physical page of iteration (64*c + i).
     auto load_table = [&](int base_iter) {
-      int pg = first + (base_iter + lane) * kWaves;
+      const int it = base_iter + lane;
+      const int pg = it < n_iter ? page_of(it) : pe;
       int e = pg < pe ? table[pg] : 0;
       return min(max(e, 0), p.n_pages - 1);
     };
@@ -168,7 +180,7 @@ __device__ __forceinline__ void attn_split_body(const AttnParams& p, const int g
     load_page(cur, p.kpool, p.vpool, __builtin_amdgcn_readlane(tbl, 0), p.Hkv, g, lane);
 
     for (int it = 0; it < n_iter; ++it) {
-      const int pg = first + it * kWaves;
+      const int pg = page_of(it);
       if (it + 1 < n_iter) {
         if (((it + 1) & 63) == 0) tbl = load_table(it + 1);
         load_page(nxt, p.kpool, p.vpool, __builtin_amdgcn_readlane(tbl, (it + 1) & 63), p.Hkv, g, lane);

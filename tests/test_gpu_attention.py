@@ -214,3 +214,26 @@ def test_verify_four_tokens_full_size_sampled_rows():
         got = gpu_attention(q, kp, vp, table, lens, T, window, max_len, n_pages=n_pages)
         assert np.isfinite(got).all()
         _check_sampled_rows(got, q, kp, vp, table, lens, window, [(0, 0), (3, 17), (15, 31), (7, 9)])
+
+
+@pytest.mark.parametrize("window", [0, 300])
+def test_regular_page_tables_and_many_ranges(window):
+    """Pages of a sequence in a row, sequences at a fixed distance (a freshly filled cache) and, second, pages
+    interleaved over the sequences (caches that grew together): every workgroup visits its range from its own
+    starting point, so the result must not depend on how regular the table is."""
+    B, T, max_len = 5, 2, 3000
+    max_pages = (max_len + 15) // 16
+    lens = np.array([3000, 2999, 1, 1717, 48], dtype=np.int32)
+    p = gen.attention_inputs(4100, B, T, HQ, HKV, D, lens, max_pages)
+    for kind in ("rows", "interleaved"):
+        if kind == "rows":
+            table = np.arange(B * max_pages, dtype=np.int32).reshape(B, max_pages)
+        else:
+            table = (np.arange(max_pages, dtype=np.int32)[None, :] * B + np.arange(B, dtype=np.int32)[:, None])
+        n_pages = B * max_pages
+        klog, vlog = gen.logical_pools(p["k_tok"], p["v_tok"], table, lens, n_pages)
+        kphys, vphys = kl.to_physical(klog, vlog)
+        got = gpu_attention(p["q"], dev(kphys), dev(vphys), table, lens, T, window, max_len, n_pages=n_pages)
+        ref = om.attn_decode(p["q"], klog, vlog, table, lens, window, D ** -0.5)
+        for b in range(B):
+            assert rel_err(got[b], ref[b]) <= OUT_TOL, (kind, b)
