@@ -118,8 +118,13 @@ __device__ __forceinline__ void attn_split_body(const AttnParams& p, const int g
   const int lo_first = p.window > 0 ? max(0, L - p.T + 1 - p.window) : 0;
   const int page_first = lo_first / kPage;
   const int page_end = (L + kPage - 1) / kPage;
-  const int ps = page_first + split * p.pages_per_split;
-  const int pe = min(page_end, ps + p.pages_per_split);
+  // The page ranges are cut from the sequence's own length (known only here), so that all ranges of a (request, KV head)
+  // carry the same work and a short sequence becomes several short ranges instead of one long and some empty ones;
+  // the host's pages_per_split, planned from the longest possible sequence, is the upper limit.
+  const int own = (((page_end - page_first + p.nsplit - 1) / p.nsplit) + kWaves - 1) / kWaves * kWaves;
+  const int per_split = min(max(own, kWaves), p.pages_per_split);
+  const int ps = page_first + split * per_split;
+  const int pe = min(page_end, ps + per_split);
 
   // This lane's query row in tile n: new token t_row, head g*G + row%G.  Rows >= R are padding (q = 0).
   bool real_row[NT];
