@@ -34,10 +34,14 @@ __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
     // KV head fastest, then page range, then request: the order of the stand-alone grid
     const int pairs = i / a.Hkv;
     attn_split_body<1>(a, i - pairs * a.Hkv, pairs % a.nsplit, pairs / a.nsplit, sm);
-  } else if (id < p.end_kda) {
-    delta_step_body<128, 128, true, false>(p.kda, id - p.end_swa);
   } else {
-    delta_step_body<128, 128, false, false>(p.gdn, id - p.end_kda);
+    // the recurrent tiles of both mixers as one list, visited as the stand-alone step kernels visit theirs
+    const int tile = interleaved_tile(id - p.end_swa, static_cast<int>(gridDim.x) - p.end_swa);
+    const int n_kda = p.end_kda - p.end_swa;
+    if (tile < n_kda)
+      delta_step_body<128, 128, true, false>(p.kda, tile);
+    else
+      delta_step_body<128, 128, false, false>(p.gdn, tile - n_kda);
   }
 }
 
@@ -49,7 +53,7 @@ struct RecurrentLayerParams {
 };
 
 __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
-  const int id = blockIdx.x;
+  const int id = interleaved_tile(blockIdx.x, gridDim.x);  // as the stand-alone step kernels visit their tiles
   if (id < p.end_kda)
     delta_step_body<128, 128, true, false>(p.kda, id);
   else
