@@ -108,16 +108,20 @@ namespace {
 
 // The memory traffic of the recurrent decode step and nothing else: one workgroup per 64 KiB tile, the lane
 // pattern and non-temporal accesses of delta_step_kernel (lane (r8, c8) of wavefront w owns columns
-// 32w + 4c8 .. +3 of rows 16 r8 .. 16 r8 + 15).  KIND 0 reads the tile, 1 writes it, 2 reads, scales and writes it back.
+// 32w + 4c8 .. +3 of rows 16 r8 .. 16 r8 + 15, walked from a row that differs between neighbouring workgroups, and
+// the tile list is visited in four interleaved quarters).  KIND 0 reads the tile, 1 writes it, 2 reads, scales and
+// writes it back.
 template <int KIND>
 __global__ __launch_bounds__(256) void stream_tiles_kernel(float* tiles, float factor) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int c8 = lane & 7, r8 = lane >> 3;
-  float* p = tiles + static_cast<size_t>(blockIdx.x) * (128 * 128) + (r8 * 16) * 128 + wave * 32 + c8 * 4;
+  const int tile = interleaved_tile(blockIdx.x, gridDim.x);
+  const int turn4 = 4 * (blockIdx.x & 3);
+  float* p = tiles + static_cast<size_t>(tile) * (128 * 128) + (r8 * 16) * 128 + wave * 32 + c8 * 4;
   float4 s[16];
   if (KIND != 1) {
 #pragma unroll
-    for (int m = 0; m < 16; ++m) s[m] = load_state(p + m * 128);
+    for (int m = 0; m < 16; ++m) s[m] = load_state(p + ((m + turn4) & 15) * 128);
   }
   if (KIND == 0) {
     float acc = 0.f;
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(256) void stream_tiles_kernel(float* tiles, float f
       s[m].z *= factor;
       s[m].w *= factor;
     }
-    store_state(p + m * 128, s[m]);
+    store_state(p + ((m + turn4) & 15) * 128, s[m]);
   }
 }
 

@@ -70,6 +70,9 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
 
   const sa_block_io& io = p.io;
   const int tile_id = interleaved_tile(blockIdx.x, gridDim.x);
+  // register m of a lane holds row (m + turn4) mod RPL of its rows, as in the plain step kernel: neighbouring
+  // workgroups do not all fetch the same slice of their tiles at the same moment
+  const int turn4 = 4 * (blockIdx.x & (RPL / 4 - 1));
   const int r = tile_id / p.H;
   const int h = tile_id - r * p.H;
   const int b = p.req_idx ? p.req_idx[r] : r;
@@ -87,7 +90,7 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
   float* sout = p.state_out + tile + static_cast<size_t>(row0) * DV + col0;
   float4 s[RPL];
 #pragma unroll
-  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + m * DV);
+  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + turn4) & (RPL - 1)) * DV);
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- pre-processing: one q or k channel and (first half of the threads) one v channel per thread
@@ -127,8 +130,8 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
   float kf[RPL], qf[RPL];
 #pragma unroll
   for (int i = 0; i < RPL; ++i) {
-    kf[i] = sh_k[row0 + i] * kinv;
-    qf[i] = sh_q[row0 + i] * qinv;
+    kf[i] = sh_k[row0 + ((i + turn4) & (RPL - 1))] * kinv;
+    qf[i] = sh_q[row0 + ((i + turn4) & (RPL - 1))] * qinv;
   }
   const float4 vv = *reinterpret_cast<const float4*>(&sh_v[col0]);
   const float beta = sigmoidf(io.beta_raw[static_cast<size_t>(b) * p.H + h]);
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
   if constexpr (KDA) {
 #pragma unroll
     for (int m = 0; m < RPL; ++m) {
-      const float a = sh_a[row0 + m];
+      const float a = sh_a[row0 + ((m + turn4) & (RPL - 1))];
       s[m].x *= a;
       s[m].y *= a;
       s[m].z *= a;
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
     s[m].y = fmaf(kf[m], d.y, s[m].y);
     s[m].z = fmaf(kf[m], d.z, s[m].z);
     s[m].w = fmaf(kf[m], d.w, s[m].w);
-    store_state(sout + m * DV, s[m]);
+    store_state(sout + ((m + turn4) & (RPL - 1)) * DV, s[m]);
   }
 
   // ---- gated RMS norm of the read-out (every lane holds the 4 columns of its c8; r8 copies agree)

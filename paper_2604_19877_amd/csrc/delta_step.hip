@@ -20,7 +20,7 @@ namespace {
 
 template <int DK, int DV, bool KDA, bool MULTI>
 __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
-  delta_step_body<DK, DV, KDA, MULTI>(p, interleaved_tile(blockIdx.x, gridDim.x));
+  delta_step_body<DK, DV, KDA, MULTI>(p, interleaved_tile(blockIdx.x, gridDim.x), blockIdx.x);
 }
 
 constexpr int kChunkedFrom = 5;  // tokens per call from which the decode steps run on the chunk-parallel kernels

@@ -48,21 +48,21 @@ using sa::DeltaParams;
 // Operands of one step as they arrive from memory (bf16 still packed).
 template <int RPL>
 struct StepOperands {
-  uint4 k[RPL / 8], q[RPL / 8];
+  uint2 k[RPL / 4], q[RPL / 4];  // chunk j: the 4 rows this lane holds in registers 4j .. 4j+3
   float alpha, beta;  // alpha: the scalar gate of GDN (KDA's gate vector is fetched apart)
   uint2 v;
 };
 
 template <int DK, int DV, bool KDA>
 __device__ __forceinline__ void load_operands(StepOperands<DK / 8>& o, const DeltaParams& p, size_t bt, int h, int hk, int row0,
-                                              int col0) {
+                                              int col0, int turn) {
   constexpr int RPL = DK / 8;
-  const uint4* kp = reinterpret_cast<const uint4*>(p.k + (bt * p.Hk + hk) * DK + row0);
-  const uint4* qp = reinterpret_cast<const uint4*>(p.q + (bt * p.Hk + hk) * DK + row0);
+  const uint2* kp = reinterpret_cast<const uint2*>(p.k + (bt * p.Hk + hk) * DK + row0);
+  const uint2* qp = reinterpret_cast<const uint2*>(p.q + (bt * p.Hk + hk) * DK + row0);
 #pragma unroll
-  for (int i = 0; i < RPL / 8; ++i) {
-    o.k[i] = kp[i];
-    o.q[i] = qp[i];
+  for (int j = 0; j < RPL / 4; ++j) {
+    o.k[j] = kp[(j + turn) & (RPL / 4 - 1)];
+    o.q[j] = qp[(j + turn) & (RPL / 4 - 1)];
   }
   o.v = *reinterpret_cast<const uint2*>(p.v + (bt * p.H + h) * DV + col0);
   o.beta = load_uniform(p.beta, bt * p.H + h);
@@ -71,22 +71,20 @@ __device__ __forceinline__ void load_operands(StepOperands<DK / 8>& o, const Del
 
 // KDA's gates of this lane's rows for one step.
 template <int DK>
-__device__ __forceinline__ void load_gate_vector(float4 (&a)[DK / 32], const DeltaParams& p, size_t bt, int h, int row0) {
+__device__ __forceinline__ void load_gate_vector(float4 (&a)[DK / 32], const DeltaParams& p, size_t bt, int h, int row0, int turn) {
   const float4* ap = reinterpret_cast<const float4*>(p.alpha + (bt * p.H + h) * DK + row0);
 #pragma unroll
-  for (int i = 0; i < DK / 32; ++i) a[i] = ap[i];
+  for (int j = 0; j < DK / 32; ++j) a[j] = ap[(j + turn) & (DK / 32 - 1)];
 }
 
 template <int N>
-__device__ __forceinline__ void unpack_bf16(const uint4 (&src)[N / 8], float (&dst)[N]) {
+__device__ __forceinline__ void unpack_bf16(const uint2 (&src)[N / 4], float (&dst)[N]) {
 #pragma unroll
-  for (int i = 0; i < N / 8; ++i) {
-    const uint32_t w[4] = {src[i].x, src[i].y, src[i].z, src[i].w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      dst[8 * i + 2 * e] = bf16_lo(w[e]);
-      dst[8 * i + 2 * e + 1] = bf16_hi(w[e]);
-    }
+  for (int j = 0; j < N / 4; ++j) {
+    dst[4 * j] = bf16_lo(src[j].x);
+    dst[4 * j + 1] = bf16_hi(src[j].x);
+    dst[4 * j + 2] = bf16_lo(src[j].y);
+    dst[4 * j + 3] = bf16_hi(src[j].y);
   }
 }
 
@@ -95,8 +93,12 @@ __device__ __forceinline__ void unpack_bf16(const uint4 (&src)[N / 8], float (&d
 // operands of step t+1 are requested before step t is computed.
 // The work of one workgroup (2*DV threads): tile `block` = (row of the request list) * H + head.
 template <int DK, int DV, bool KDA, bool MULTI>
-__device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int block) {
+__device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int block, const int start) {
   constexpr int RPL = DK / 8;  // rows per lane
+  // Register m of a lane holds row (m + 4 * turn) mod RPL of the lane's rows: workgroups launched next to each other
+  // take different turns, so that at any moment they are not all fetching the same 512-byte slice of their tiles
+  // (all tiles are 64 KiB apart, so those slices would all sit on the same few memory channels).
+  const int turn = start & (RPL / 4 - 1);
   const int r = block / p.H;
   const int h = block - r * p.H;
   const int b = p.req_idx ? p.req_idx[r] : r;
@@ -121,22 +123,22 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   // would put a full memory latency on the critical path of every tile.
   StepOperands<RPL> cur, nxt;
   float4 gate_vec[RPL / 4];  // KDA only: single-buffered, the next step's is requested as soon as this step's is applied
-  load_operands<DK, DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0);
-  if constexpr (KDA) load_gate_vector<DK>(gate_vec, p, static_cast<size_t>(b) * T, h, row0);
+  load_operands<DK, DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0, turn);
+  if constexpr (KDA) load_gate_vector<DK>(gate_vec, p, static_cast<size_t>(b) * T, h, row0, turn);
   float4 s[RPL];
 #pragma unroll
-  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + m * DV);
+  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + 4 * turn) & (RPL - 1)) * DV);
   __builtin_amdgcn_sched_barrier(0);
 
   if (MULTI && n_commit == 0 && p.state_out != p.state_in) {
 #pragma unroll
-    for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
+    for (int m = 0; m < RPL; ++m) store_state(sout + ((m + 4 * turn) & (RPL - 1)) * DV, s[m]);
   }
 
   for (int t = 0; t < T; ++t) {
     const size_t bt = static_cast<size_t>(b) * T + t;
     if constexpr (MULTI) {
-      if (t + 1 < T) load_operands<DK, DV, KDA>(nxt, p, bt + 1, h, hk, row0, col0);
+      if (t + 1 < T) load_operands<DK, DV, KDA>(nxt, p, bt + 1, h, hk, row0, col0, turn);
       __builtin_amdgcn_sched_barrier(0);
     }
     float kf[RPL], qf[RPL];
@@ -159,7 +161,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
         }
       }
       if constexpr (MULTI) {
-        if (t + 1 < T) load_gate_vector<DK>(gate_vec, p, bt + 1, h, row0);
+        if (t + 1 < T) load_gate_vector<DK>(gate_vec, p, bt + 1, h, row0, turn);
       }
     } else {
       const float a = cur.alpha;
@@ -210,7 +212,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
     }
     if (!MULTI || t + 1 == n_commit) {
 #pragma unroll
-      for (int m = 0; m < RPL; ++m) store_state(sout + m * DV, s[m]);
+      for (int m = 0; m < RPL; ++m) store_state(sout + ((m + 4 * turn) & (RPL - 1)) * DV, s[m]);
     }
     if (r8 == 0) {
       float4 o;

@@ -39,9 +39,9 @@ __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
     const int tile = interleaved_tile(id - p.end_swa, static_cast<int>(gridDim.x) - p.end_swa);
     const int n_kda = p.end_kda - p.end_swa;
     if (tile < n_kda)
-      delta_step_body<128, 128, true, false>(p.kda, tile);
+      delta_step_body<128, 128, true, false>(p.kda, tile, blockIdx.x);
     else
-      delta_step_body<128, 128, false, false>(p.gdn, tile - n_kda);
+      delta_step_body<128, 128, false, false>(p.gdn, tile - n_kda, blockIdx.x);
   }
 }
 
@@ -55,9 +55,9 @@ struct RecurrentLayerParams {
 __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
   const int id = interleaved_tile(blockIdx.x, gridDim.x);  // as the stand-alone step kernels visit their tiles
   if (id < p.end_kda)
-    delta_step_body<128, 128, true, false>(p.kda, id);
+    delta_step_body<128, 128, true, false>(p.kda, id, blockIdx.x);
   else
-    delta_step_body<128, 128, false, false>(p.gdn, id - p.end_kda);
+    delta_step_body<128, 128, false, false>(p.gdn, id - p.end_kda, blockIdx.x);
 }
 
 struct MergeParams {
