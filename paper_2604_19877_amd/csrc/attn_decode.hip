@@ -167,6 +167,7 @@ sa_status sa::attn_prepare(const void* q, const void* kpool, const void* vpool, 
   SA_REQUIRE(need == 0 || workspace, SA_EINVAL, "%s: workspace is null", name);
   SA_REQUIRE(workspace_bytes >= need, SA_EWORKSPACE, "%s: workspace has %zu bytes, %zu needed", name, workspace_bytes, need);
   SA_REQUIRE(rows <= 65535 && Hkv <= 65535, SA_EUNSUPPORTED, "%s: more than 65535 rows or KV heads per launch", name);
+  SA_REQUIRE(static_cast<long long>(rows) * Hkv * R <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: rows*Hkv*T*(Hq/Hkv) too large for one launch", name);
   if (!launch) return SA_OK;
 
   AttnParams& p = launch->p;

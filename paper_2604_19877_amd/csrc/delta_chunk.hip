@@ -88,6 +88,13 @@ __device__ __forceinline__ bf16x8 join8(const u32x2& a, const u32x2& b) {
   return __builtin_bit_cast(bf16x8, u32x4{a[0], a[1], b[0], b[1]});
 }
 
+// K^T Delta with Delta as two bf16 terms in ONE 16x16x32 product: the contraction index of the wide instruction
+// runs over (token, term), slots 0-3 of a lane's 8 holding tokens 4g..4g+3 with the first term of Delta and
+// slots 4-7 the same tokens with the second, so the A operand is the lane's 4 K values twice.
+__device__ __forceinline__ f32x4 mfma_two_terms(const u32x2& a, const Split4x2& b, const f32x4& acc) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(join8(a, a), join8(b.hi, b.lo), acc, 0, 0, 0);
+}
+
 // Orders this wavefront's LDS writes before its later LDS reads by other lanes.
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -140,8 +147,7 @@ __device__ __forceinline__ void readout_rows(f32x4 (&o)[2], const f32x4 (&delta)
   for (int c = 0; c < 2; ++c) {
     const Split4x2 dl = split2(delta[c]);
     o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.lo), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
-    o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.lo), o[c], 0, 0, 0);
-    o[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, ms.hi), __builtin_bit_cast(s16x4, dl.hi), o[c], 0, 0, 0);
+    o[c] = mfma_two_terms(ms.hi, dl, o[c]);
   }
 }
 
@@ -370,15 +376,14 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       }
 #pragma unroll
       for (int rt = 0; rt < 8; ++rt) {
-        const s16x4 kt = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g));
+        const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g);
         f32x4 acc[2];
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
           acc[c] = S[rt][c];
 #pragma unroll
           for (int j = 0; j < 4; ++j) acc[c][j] *= g_keep;
-          acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, dk2[c].lo), acc[c], 0, 0, 0);
-          acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, dk2[c].hi), acc[c], 0, 0, 0);
+          acc[c] = mfma_two_terms(kt, dk2[c], acc[c]);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -399,15 +404,13 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     }
 #pragma unroll
     for (int rt = 0; rt < 8; ++rt) {
-      const s16x4 kt = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g));
+      const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g);
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         f32x4 acc = S[rt][c];
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[j] *= g_chunk;
-        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].lo), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kt, __builtin_bit_cast(s16x4, ds[c].hi), acc, 0, 0, 0);
-        S[rt][c] = acc;
+        S[rt][c] = mfma_two_terms(kt, ds[c], acc);
       }
     }
     cur = nxt;
@@ -696,7 +699,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
 #pragma unroll
       for (int rt = 0; rt < 8; ++rt) {
         const int at = (16 * rt + n) * kChRowB + 8 * g;
-        const s16x4 e_hi = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(kend_hi + at));
+        const u32x2 e_hi = *reinterpret_cast<const u32x2*>(kend_hi + at);
         const s16x4 e_lo = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(kend_lo + at));
         const f32x4 row_scale = *reinterpret_cast<const f32x4*>(p_end + 16 * rt + 4 * g);
 #pragma unroll
@@ -705,9 +708,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) acc[j] *= row_scale[j];
           acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(e_lo, __builtin_bit_cast(s16x4, ds[c].hi), acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(e_hi, __builtin_bit_cast(s16x4, ds[c].lo), acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(e_hi, __builtin_bit_cast(s16x4, ds[c].hi), acc, 0, 0, 0);
-          S[rt][c] = acc;
+          S[rt][c] = mfma_two_terms(e_hi, ds[c], acc);
         }
       }
       first = stop;

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(128) void layer_merge_kernel(MergeParams p) {
 sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch& swa, const sa::DeltaLaunch& kda,
                                  const sa::DeltaLaunch& gdn, void* stream) {
   const char* name = "placement_decode (fused layer)";
-  LayerParams p;
+  LayerParams p = {};
   p.fa = fa.p;
   p.swa = swa.p;
   p.kda = kda.p;
@@ -101,20 +101,19 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
     sa::launch(SA_K_LAYER, layer_recurrent_kernel, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, rp);
     return sa::check_launch(name);
   }
+  const long long m_fa = fa.rows && fa.p.nsplit > 1 ? static_cast<long long>(fa.rows) * fa.p.Hkv * fa.p.R : 0;
+  const long long m_swa = swa.rows && swa.p.nsplit > 1 ? static_cast<long long>(swa.rows) * swa.p.Hkv * swa.p.R : 0;
+  SA_REQUIRE(m_fa + m_swa <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many rows to merge in one layer", name);
   p.end_fa = static_cast<int>(n_fa);
   p.end_swa = static_cast<int>(n_fa + n_swa);
   p.end_kda = static_cast<int>(n_fa + n_swa + n_kda);
   sa::launch(SA_K_LAYER, layer_decode_kernel, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
   sa_status st = sa::check_launch(name);
-  if (st != SA_OK) return st;
+  if (st != SA_OK || m_fa + m_swa == 0) return st;
 
   MergeParams m;
   m.fa = fa.p;
   m.swa = swa.p;
-  const long long m_fa = fa.rows && fa.p.nsplit > 1 ? static_cast<long long>(fa.rows) * fa.p.Hkv * fa.p.R : 0;
-  const long long m_swa = swa.rows && swa.p.nsplit > 1 ? static_cast<long long>(swa.rows) * swa.p.Hkv * swa.p.R : 0;
-  if (m_fa + m_swa == 0) return SA_OK;
-  SA_REQUIRE(m_fa + m_swa <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many rows to merge in one layer", name);
   m.end_fa = static_cast<int>(m_fa);
   sa::launch(SA_K_ATTN_MERGE, layer_merge_kernel, dim3(static_cast<unsigned>(m_fa + m_swa)), dim3(128), 0, s, m);
   return sa::check_launch("placement_decode (fused merge)");

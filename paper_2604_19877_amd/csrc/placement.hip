@@ -142,9 +142,8 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
       // One fused launch when the layer mixes mixers (measured from batch 8 / 2048-token contexts to batch 128 /
       // 16384: 26 % to 0 % faster than one launch per mixer).
       if (can_fuse && present >= 2 && !x.n_commit_rows) {
-        sa::AttnLaunch fa, swa;
-        sa::DeltaLaunch kda, gdn;
-        fa.rows = swa.rows = kda.rows = gdn.rows = 0;
+        sa::AttnLaunch fa = {}, swa = {};
+        sa::DeltaLaunch kda = {}, gdn = {};
         sa_status st = SA_OK;
         if (cnt[0])
           st = sa::attn_prepare(x.q_attn, x.kpool, x.vpool, x.n_pages, x.page_table, x.max_pages, x.seq_lens, lists[0], cnt[0], x.out, B,
