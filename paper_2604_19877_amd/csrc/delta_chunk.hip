@@ -151,15 +151,15 @@ __device__ __forceinline__ void readout_rows(f32x4 (&o)[2], const f32x4 (&delta)
   }
 }
 
-// Writes this lane's part of the state tile (accumulator layout) with the non-temporal hint.  The offset is
-// made opaque so that the 32 store addresses are formed here and not kept in registers from the kernel's start.
-__device__ __forceinline__ void store_tile(const f32x4 (&S)[8][2], float* sout, uint32_t lane_off) {
+// Writes this lane's part of the state tile (accumulator layout), times `factor`, with the non-temporal hint.  The
+// offset is made opaque so that the 32 store addresses are formed here and not kept in registers from the kernel's start.
+__device__ __forceinline__ void store_tile(const f32x4 (&S)[8][2], float* sout, uint32_t lane_off, float factor = 1.f) {
   asm volatile("" : "+v"(lane_off));
 #pragma unroll
   for (int rt = 0; rt < 8; ++rt)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const f32x2 x = {S[rt][0][j], S[rt][1][j]};
+      const f32x2 x = {factor * S[rt][0][j], factor * S[rt][1][j]};
       __builtin_nontemporal_store(x, reinterpret_cast<f32x2*>(sout + (lane_off + (16 * rt + j) * kD)));
     }
 }
@@ -177,35 +177,56 @@ struct ChunkFetch {
   float alpha, beta;  // of token lane%16
 };
 
-// Tokens past the end of the call are read from the last valid token (always in bounds) and then
-// replaced by values that leave the state alone: k = q = v = 0, alpha = 1, beta = 0.  All addresses are
-// a per-chunk scalar base plus a 32-bit lane offset (a chunk spans < 4 GiB).
-__device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p, size_t row0, int t0, int h, int hk, int col,
-                                            int g, int n) {
+// Byte offsets of a thread's loads from the chunk's first token, with tokens past `lim` (the last valid token of
+// the chunk) redirected to token `lim`, which is always in bounds.
+struct ChunkOffsets {
+  uint32_t kq, v[4], gate;
+};
+__device__ __forceinline__ ChunkOffsets chunk_offsets(const ChunkParams& p, int lim, int col, int g, int n) {
   const int tid = threadIdx.x;
   const int tok = tid >> 4, c8 = (tid & 15) * 8;
-  const int lim = p.T - 1 - t0;  // last valid token of the chunk
-  {
-    const size_t base = ((row0 + t0) * p.Hk + hk) * kD;
-    const uint32_t off = (static_cast<uint32_t>(min(tok, lim)) * static_cast<uint32_t>(p.Hk * kD) + c8) * 2u;
-    const u32x4 kk = load_at<u32x4>(p.k + base, off), qq = load_at<u32x4>(p.q + base, off);
-    const bool live = tok <= lim;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      f.kst[e] = live ? kk[e] : 0u;
-      f.qst[e] = live ? qq[e] : 0u;
-    }
-  }
-  const size_t base = (row0 + t0) * p.H + h;
+  ChunkOffsets o;
+  o.kq = (static_cast<uint32_t>(min(tok, lim)) * static_cast<uint32_t>(p.Hk * kD) + c8) * 2u;
   const uint32_t stride = static_cast<uint32_t>(p.H * kD);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int t = 4 * g + j;
-    const uint32_t x = load_at<uint32_t>(p.v + base * kD, (static_cast<uint32_t>(min(t, lim)) * stride + col) * 2u);
-    f.v[j] = t <= lim ? x : 0u;
+  for (int j = 0; j < 4; ++j) o.v[j] = (static_cast<uint32_t>(min(4 * g + j, lim)) * stride + col) * 2u;
+  o.gate = static_cast<uint32_t>(min(n, lim)) * static_cast<uint32_t>(p.H) * 4u;
+  return o;
+}
+
+// All addresses are a per-chunk scalar base plus a 32-bit lane offset (a chunk spans < 4 GiB).  `full` holds the
+// offsets of a chunk that lies wholly inside the call (computed once per kernel).  The call's last chunk may be
+// ragged: tokens past the end are read from the last valid token and then replaced by values that leave the
+// state alone: k = q = v = 0, alpha = 1, beta = 0.
+__device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p, const ChunkOffsets& full, size_t row0, int t0, int h,
+                                            int hk, int col, int g, int n) {
+  const int lim = p.T - 1 - t0;  // last valid token of the chunk
+  const size_t kq_base = ((row0 + t0) * p.Hk + hk) * kD;
+  const size_t base = (row0 + t0) * p.H + h;
+  if (lim >= kC - 1) {
+    f.kst = load_at<u32x4>(p.k + kq_base, full.kq);
+    f.qst = load_at<u32x4>(p.q + kq_base, full.kq);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f.v[j] = load_at<uint32_t>(p.v + base * kD, full.v[j]);
+    f.alpha = load_at<float>(p.alpha + base, full.gate);
+    f.beta = load_at<float>(p.beta + base, full.gate);
+    return;
   }
-  const uint32_t gi = static_cast<uint32_t>(min(n, lim)) * static_cast<uint32_t>(p.H) * 4u;
-  const float a = load_at<float>(p.alpha + base, gi), bt = load_at<float>(p.beta + base, gi);
+  const ChunkOffsets o = chunk_offsets(p, lim, col, g, n);
+  const int tok = static_cast<int>(threadIdx.x) >> 4;
+  const u32x4 kk = load_at<u32x4>(p.k + kq_base, o.kq), qq = load_at<u32x4>(p.q + kq_base, o.kq);
+  const bool live = tok <= lim;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f.kst[e] = live ? kk[e] : 0u;
+    f.qst[e] = live ? qq[e] : 0u;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t x = load_at<uint32_t>(p.v + base * kD, o.v[j]);
+    f.v[j] = 4 * g + j <= lim ? x : 0u;
+  }
+  const float a = load_at<float>(p.alpha + base, o.gate), bt = load_at<float>(p.beta + base, o.gate);
   f.alpha = n <= lim ? a : 1.f;
   f.beta = n <= lim ? bt : 0.f;
 }
@@ -236,8 +257,11 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
   float* const sout = p.state_out + tile;
   const uint32_t lane_off = static_cast<uint32_t>(4 * g * kD + col);
 
+  // Kept in registers for the whole call (the empty asm stops the compiler from recomputing them per chunk).
+  ChunkOffsets full = chunk_offsets(p, kC - 1, col, g, n);
+  asm volatile("" : "+v"(full.kq), "+v"(full.v[0]), "+v"(full.v[1]), "+v"(full.v[2]), "+v"(full.v[3]), "+v"(full.gate));
   ChunkFetch cur, nxt;
-  fetch_chunk(cur, p, row0, 0, h, hk, col, g, n);
+  fetch_chunk(cur, p, full, row0, 0, h, hk, col, g, n);
   // S[rt][c][j]: key row 16 rt + 4 g + j, value column col + c.
   f32x4 S[8][2];
 #pragma unroll
@@ -250,11 +274,15 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     }
   __builtin_amdgcn_sched_barrier(0);
 
+  // The registers hold the state divided by 2^c_log: a chunk's decay g(15,-1) goes into that common factor
+  // instead of into 64 multiplications per lane, and the factor is multiplied in once it falls below 2^-96
+  // (and wherever the state is stored).  The factor is the same for the whole workgroup.
+  float c_log = 0.f;
   const int n_chunks = (p.T + kC - 1) / kC;
   for (int ch = 0; ch < n_chunks; ++ch) {
     const int t0 = ch * kC;
     const int n_keep = n_commit - t0;  // tokens of this chunk that the stored state includes, if it is stored here
-    if (n_keep == 0 && n_commit < p.T && (t0 > 0 || sout != sin)) store_tile(S, sout, lane_off);
+    if (n_keep == 0 && n_commit < p.T && (t0 > 0 || sout != sin)) store_tile(S, sout, lane_off, exp2f(c_log));
     unsigned char* const stage = lds + (ch & 1) * kStageB;
     unsigned char* const k_tok = stage;                       // [16 tokens][kTokRowB]
     unsigned char* const q_tok = stage + kC * kTokRowB;
@@ -276,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       // An opaque copy of the next chunk's first token keeps the address arithmetic here, in scalar registers.
       int t_next = t0 + kC;
       asm volatile("" : "+s"(t_next));
-      fetch_chunk(nxt, p, row0, t_next, h, hk, col, g, n);
+      fetch_chunk(nxt, p, full, row0, t_next, h, hk, col, g, n);
     }
 
     // K S_0 and Q S_0 for this wavefront's 32 columns (rows = tokens 4g+j), and the Gram matrices
@@ -311,17 +339,21 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       const float y = __shfl_up(log_sum, d, 16);
       log_sum += n >= d ? y : 0.f;
     }
-    const float log_chunk = __shfl(log_sum, 15);
+    const float log_chunk = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, __shfl(log_sum, 15))));
+    // Fold the common factor in now if this chunk's decay would take it below 2^-96; otherwise the corrections
+    // are divided by the new factor instead, which multiplies them by at most 2^96.
+    const float c_next = c_log + log_chunk;
+    const bool fold = c_next < -96.f;
+    const float end_base = fold ? log_chunk : -c_log;
     float g_start[4], g_end[4], beta_t[4], ratio[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float lt = __shfl(log_sum, 4 * g + j);
-      g_start[j] = exp2f(lt);
-      g_end[j] = exp2f(log_chunk - lt);
+      g_start[j] = exp2f(lt + c_log);       // g(t,-1) times the common factor: applies to products with the registers' state
+      g_end[j] = exp2f(end_base - lt);      // g(15,t) over the factor the registers carry after this chunk
       ratio[j] = exp2f(fminf(lt - log_sum, 0.f));  // g(t,n) for t = 4g+j >= n (unused otherwise)
       beta_t[j] = __shfl(cur.beta, 4 * g + j);
     }
-    const float g_chunk = exp2f(log_chunk);
     const bool own_group = (n >> 2) == g;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -362,7 +394,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       uint32_t keep_off = lane_off;
       asm volatile("" : "+v"(keep_off));
       const float log_keep = __shfl(log_sum, n_keep - 1);
-      const float g_keep = exp2f(log_keep);
+      const float g_keep = exp2f(log_keep + c_log);
       Split4x2 dk2[2];
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
@@ -393,7 +425,19 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       }
     }
 
-    // S <- g(15,-1) S + K^T (g(15,t) delta_t): rows of the B operand are tokens.
+    // S <- g(15,-1) S + K^T (g(15,t) delta_t), the decay going into the common factor: rows of the B operand are tokens.
+    if (fold) {
+      const float f = exp2f(c_next);
+#pragma unroll
+      for (int rt = 0; rt < 8; ++rt)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) S[rt][c][j] *= f;
+      c_log = 0.f;
+    } else {
+      c_log = c_next;
+    }
     Split4x2 ds[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -407,17 +451,14 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g);
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        f32x4 acc = S[rt][c];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] *= g_chunk;
-        S[rt][c] = mfma_two_terms(kt, ds[c], acc);
+        S[rt][c] = mfma_two_terms(kt, ds[c], S[rt][c]);
       }
     }
     cur = nxt;
     // The per-wavefront matrices are rewritten in the next chunk only after this chunk's reads (program order).
   }
 
-  if (n_commit == p.T) store_tile(S, sout, lane_off);
+  if (n_commit == p.T) store_tile(S, sout, lane_off, exp2f(c_log));
 }
 
 

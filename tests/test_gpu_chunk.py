@@ -98,6 +98,31 @@ def test_vanishing_gates_stay_finite(kda):
     assert rel_err(S, S_ref) <= STATE_TOL
 
 
+@pytest.mark.parametrize("kda", KINDS)
+@pytest.mark.parametrize("n_commit", [None, 0, 603, 608])
+def test_moderate_decay_over_many_chunks(kda, n_commit):
+    """Gates around 0.9 over 44 chunks: the decay accumulated since the call's start passes 2^-96 once and is far
+    from 1 where the committed prefix ends (inside a chunk, and on a chunk's boundary)."""
+    B, H, T = 1, 2, 700
+    p = gen.recurrent_inputs(4560 + kda, B, T, H, H, 128, 128, kda)
+    rng = np.random.default_rng(4561)
+    p["alpha"] = rng.uniform(0.85, 0.95, p["alpha"].shape).astype(np.float32)
+    S0 = gen.recurrent_state(4562, B * H, 128, 128).reshape(B, H, 128, 128)
+    d = {n: dev(a) for n, a in p.items()}
+    s_in, s_out = dev(S0.copy()), dev(np.full_like(S0, np.nan))
+    out = torch.full((B, T, H, 128), float("nan"), dtype=torch.float32, device="cuda")
+    FN[kda][0](d["q"], d["k"], d["v"], d["alpha"], d["beta"], s_in, s_out, out, None, None, 0, B, T, H, H, 128, 128, 0.25,
+               T if n_commit is None else n_commit)
+    torch.cuda.synchronize()
+    o_ref, S_ref = FN[kda][1](p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, 0.25)
+    if n_commit is not None:
+        cut = {n: a[:, :n_commit] for n, a in p.items()}
+        S_ref = FN[kda][1](cut["q"], cut["k"], cut["v"], cut["alpha"], cut["beta"], S0, 0.25)[1] if n_commit else S0
+    assert rel_err(host(out), o_ref) <= OUT_TOL
+    assert rel_err(host(s_out), S_ref) <= STATE_TOL
+    assert np.array_equal(host(s_in), S0)
+
+
 def test_kda_few_channels_with_tiny_gates_split_the_chunk():
     """A handful of key channels decay by 1e-9 per token while the rest follow the recipe: the product of
     gates over a chunk leaves the range in which it can be divided by, so chunks run in several passes."""
