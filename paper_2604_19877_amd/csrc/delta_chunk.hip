@@ -95,6 +95,12 @@ __device__ __forceinline__ f32x4 mfma_two_terms(const u32x2& a, const Split4x2& 
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(join8(a, a), join8(b.hi, b.lo), acc, 0, 0, 0);
 }
 
+// x of the lane D places down the same row of 16 lanes, 0 for the first D lanes of a row.
+template <int D>
+__device__ __forceinline__ float row_shr(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x110 + D, 0xf, 0xf, true));
+}
+
 // Orders this wavefront's LDS writes before its later LDS reads by other lanes.
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -333,13 +339,13 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     // Decay factors from the running sum of log2(alpha): every g(t,i) = 2^(L_t - L_i) is at most 1, so no
     // product of gates can overflow or divide by an underflowed one.  Every lane holds alpha and beta of
     // token lane%16; a gate below the smallest normal number acts as that number.
-    float log_sum = log2f(fmaxf(cur.alpha, 1.17549435e-38f));  // inclusive prefix sum L_n
-#pragma unroll
-    for (int d = 1; d < 16; d *= 2) {
-      const float y = __shfl_up(log_sum, d, 16);
-      log_sum += n >= d ? y : 0.f;
-    }
-    const float log_chunk = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, __shfl(log_sum, 15))));
+    // Inclusive prefix sum L_n over the 16 lanes of a row with row shifts (a lane without a source adds 0).
+    float log_sum = log2f(fmaxf(cur.alpha, 1.17549435e-38f));
+    log_sum += row_shr<1>(log_sum);
+    log_sum += row_shr<2>(log_sum);
+    log_sum += row_shr<4>(log_sum);
+    log_sum += row_shr<8>(log_sum);
+    const float log_chunk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, log_sum), 15));
     // Fold the common factor in now if this chunk's decay would take it below 2^-96; otherwise the corrections
     // are divided by the new factor instead, which multiplies them by at most 2^96.
     const float c_next = c_log + log_chunk;
@@ -592,15 +598,13 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
       if (tid < kD) {
         // The product keeps running past the token where it leaves the range; those entries are never used.
         float prod = 1.f;
-        int mine = n_tok;
+        int mine = n_tok;  // the first token that some channel of this wavefront refuses: a scalar, from wave-wide votes
 #pragma unroll
         for (int t = 0; t < kC; ++t) {
           prod *= t >= first ? gates[t] : 1.f;
-          mine = (prod < kMinGate && t > first) ? min(mine, t) : mine;
+          if (t > 0 && __builtin_amdgcn_ballot_w64(prod < kMinGate && t > first) != 0) mine = min(mine, t);
           p_tab[t * kTabRow + chn] = prod;
         }
-#pragma unroll
-        for (int d = 1; d < 64; d *= 2) mine = min(mine, __shfl_xor(mine, d));
         if (lane == 0) limit[wave] = mine;
       }
       __syncthreads();  // also: every wavefront has finished consuming the previous pass
