@@ -109,6 +109,9 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   const int c8 = lane & 7, r8 = lane >> 3;
   const int row0 = r8 * RPL;
   const int col0 = wave * 32 + c8 * 4;
+  constexpr bool ROTATE = !(KDA && MULTI);
+  constexpr bool LAZY = MULTI && !KDA;  // GDN over several tokens: the scalar decay is carried as a common factor
+  float carry = 1.f;
   const int T = MULTI ? p.T : 1;
   // the same for the whole workgroup: kept in a scalar register
   const int n_commit =
@@ -163,6 +166,22 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
       if constexpr (MULTI) {
         if (t + 1 < T) load_gate_vector<DK>(gate_vec, p, bt + 1, h, row0, turn);
       }
+    } else if constexpr (MULTI) {
+      // The registers hold the state divided by `carry`, the product of the gates since the last time it was
+      // multiplied in: a step then scales the 8 reduced sums and its correction instead of 64 state values.  The
+      // gate is the same for the whole workgroup, and so is the decision to multiply the product in (before it
+      // could underflow: below 2^-60).
+      carry *= cur.alpha;
+      if (carry < 8.673617e-19f) {
+#pragma unroll
+        for (int m = 0; m < RPL; ++m) {
+          s[m].x *= carry;
+          s[m].y *= carry;
+          s[m].z *= carry;
+          s[m].w *= carry;
+        }
+        carry = 1.f;
+      }
     } else {
       const float a = cur.alpha;
 #pragma unroll
@@ -188,31 +207,61 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
       w.w = fmaf(s[m].w, qf[m], w.w);
       kq = fmaf(kf[m], qf[m], kq);
     }
-    u.x = reduce_r8(u.x);
-    u.y = reduce_r8(u.y);
-    u.z = reduce_r8(u.z);
-    u.w = reduce_r8(u.w);
-    w.x = reduce_r8(w.x);
-    w.y = reduce_r8(w.y);
-    w.z = reduce_r8(w.z);
-    w.w = reduce_r8(w.w);
-    kq = reduce_r8(kq);
+    u.x = reduce_r8<ROTATE>(u.x);
+    u.y = reduce_r8<ROTATE>(u.y);
+    u.z = reduce_r8<ROTATE>(u.z);
+    u.w = reduce_r8<ROTATE>(u.w);
+    w.x = reduce_r8<ROTATE>(w.x);
+    w.y = reduce_r8<ROTATE>(w.y);
+    w.z = reduce_r8<ROTATE>(w.z);
+    w.w = reduce_r8<ROTATE>(w.w);
+    kq = reduce_r8<ROTATE>(kq);
 
+    if constexpr (LAZY) {
+      u.x *= carry;
+      u.y *= carry;
+      u.z *= carry;
+      u.w *= carry;
+      w.x *= carry;
+      w.y *= carry;
+      w.z *= carry;
+      w.w *= carry;
+    }
     float4 d;
     d.x = beta * (bf16_lo(cur.v.x) - u.x);
     d.y = beta * (bf16_hi(cur.v.x) - u.y);
     d.z = beta * (bf16_lo(cur.v.y) - u.z);
     d.w = beta * (bf16_hi(cur.v.y) - u.w);
+    {
+      // what is added to the registers: the correction over the factor they carry (its reciprocal to 1 ulp)
+      float4 ds = d;
+      if constexpr (LAZY) {
+        const float r = __builtin_amdgcn_rcpf(carry);
+        ds.x *= r;
+        ds.y *= r;
+        ds.z *= r;
+        ds.w *= r;
+      }
 #pragma unroll
-    for (int m = 0; m < RPL; ++m) {
-      s[m].x = fmaf(kf[m], d.x, s[m].x);
-      s[m].y = fmaf(kf[m], d.y, s[m].y);
-      s[m].z = fmaf(kf[m], d.z, s[m].z);
-      s[m].w = fmaf(kf[m], d.w, s[m].w);
+      for (int m = 0; m < RPL; ++m) {
+        s[m].x = fmaf(kf[m], ds.x, s[m].x);
+        s[m].y = fmaf(kf[m], ds.y, s[m].y);
+        s[m].z = fmaf(kf[m], ds.z, s[m].z);
+        s[m].w = fmaf(kf[m], ds.w, s[m].w);
+      }
     }
     if (!MULTI || t + 1 == n_commit) {
 #pragma unroll
-      for (int m = 0; m < RPL; ++m) store_state(sout + ((m + 4 * turn) & (RPL - 1)) * DV, s[m]);
+      for (int m = 0; m < RPL; ++m) {
+        float4 x = s[m];
+        if constexpr (LAZY) {
+          x.x *= carry;
+          x.y *= carry;
+          x.z *= carry;
+          x.w *= carry;
+        }
+        store_state(sout + ((m + 4 * turn) & (RPL - 1)) * DV, x);
+      }
     }
     if (r8 == 0) {
       float4 o;

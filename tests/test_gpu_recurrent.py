@@ -56,6 +56,27 @@ def test_config1_256_tokens_from_zero_state(kda, T):
     assert rel_err(S, S_ref) <= STATE_TOL
 
 
+@pytest.mark.parametrize("kda", [False, True])
+@pytest.mark.parametrize("tiny", [False, True])
+def test_four_tokens_per_call_256_tokens(kda, tiny):
+    """128x128 states, 4 tokens per call (the register-resident multi-token kernel), 64 calls: the state tolerance
+    after 256 steps; with `tiny`, a third of the gates are 1e-7, so that the product of a call's gates leaves the
+    range in which the GDN kernel carries it as a common factor of the tile."""
+    B, H, Hk, d, T, n_tok = 2, 4, 2, 128, 4, 256
+    p = stepwise_inputs(1101 + kda, n_tok // T, B, T, H, Hk, d, d, kda)
+    if tiny:
+        rng = np.random.default_rng(1102)
+        p["alpha"] = np.where(rng.random(p["alpha"].shape) < 0.33, np.float32(1e-7), p["alpha"]).astype(np.float32)
+    S0 = gen.recurrent_state(1103, B * H, d, d).reshape(B, H, d, d)
+    scale = d ** -0.5
+    o, S = run_gpu(kda, p, S0, B, T, H, Hk, d, d, scale)
+    o_ref, S_ref = FN[kda][1](as_sequence(p, "q"), as_sequence(p, "k"), as_sequence(p, "v"), as_sequence(p, "alpha"),
+                              as_sequence(p, "beta"), S0, scale)
+    assert np.isfinite(o).all() and np.isfinite(S).all()
+    assert rel_err(o, o_ref) <= OUT_TOL
+    assert rel_err(S, S_ref) <= STATE_TOL
+
+
 @pytest.mark.parametrize("kda,B", [(False, 64), (True, 64), (True, 256)])
 def test_full_shape_256_steps_sampled_tiles(kda, B):
     """15B-class shape (32 heads, 128x128 fp32 states ~ N(0, 0.02^2)), 256 consecutive steps on the
