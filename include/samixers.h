@@ -257,15 +257,19 @@ void placement_plan_destroy(sa_plan* plan);
 /* Number of requests that run mixer `mixer` ('F','S','K','G') at layer `layer`; -1 on bad arguments. */
 int placement_plan_count(const sa_plan* plan, int layer, char mixer);
 /* Bytes of device workspace placement_decode needs for this plan (0 if no layer splits its contexts into page
- * ranges): the largest sum over a layer of its full-attention and its sliding-window partial results, which a
- * fused layer launch keeps side by side. */
+ * ranges): twice the largest sum over a layer of its full-attention and its sliding-window partial results.  A
+ * fused layer launch keeps the two side by side, and alternate layers use alternate halves of the workspace,
+ * because a fused layer's partial results are merged by the launch of the layer after it. */
 size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, int T, int max_seq_len, int window);
 /* io: host array of L descriptors.  Checks the arguments of every launch of the stack first (nothing is
  * enqueued if any is bad), then enqueues layer by layer.  A one-token step (T == 1) at 128x128 states runs a layer
- * in which two or more mixers are present as one fused launch over all their request lists, followed by one merge
- * launch if an attention call has several page ranges; any other layer or step runs one launch (attention: plus a
- * merge) per mixer present.  Results do not depend on which of the two is taken.  Recurrent layers update their
- * states in place, by all T steps or by each request's n_commit_rows. */
+ * in which two or more mixers are present as one fused launch over all their request lists; if one of its
+ * attention calls has several page ranges, their partial results are merged at the head of the next fused launch
+ * (a small merge launch of its own follows only when the next layer is not fused, or none is left).  Any other
+ * layer or step runs one launch (attention: plus a merge) per mixer present.  Results do not depend on which of
+ * the two is taken, and every layer's output is complete in stream order when the call's last launch has run.
+ * Recurrent layers update their states in place, by all T steps or by each request's n_commit_rows.
+ * workspace: device memory, 256-byte aligned, at least placement_workspace_bytes(); SA_EWORKSPACE if too small. */
 sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,
                            float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes, void* stream);
 

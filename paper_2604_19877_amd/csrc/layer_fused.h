@@ -5,10 +5,22 @@
 
 namespace sa {
 
-// Enqueues one kernel that runs the prepared launches of a layer (any of them may have rows == 0) and, if an
-// attention call has several page ranges, one merge kernel.  All four must be single-token decode calls
-// (T == 1) at 128x128 states and at most 16 query rows per KV head.
+// Partial results of a layer's attention calls that still wait to be merged into the layer's output: n_fa and
+// n_swa count the (request, KV head, query row) items of each call (0: nothing to merge).
+struct PendingMerge {
+  AttnParams fa, swa;
+  int n_fa = 0, n_swa = 0;
+};
+
+// Enqueues one kernel that first merges what `pending` holds (the partial results of an earlier layer) and then
+// runs the prepared launches of this layer (any of them may have rows == 0).  On return `pending` describes this
+// layer's own partial results, to be merged by the next layer's launch or by layer_merge_flush: the buffers it
+// points to must not be written before that.  All four launches must be single-token decode calls (T == 1) at
+// 128x128 states and at most 16 query rows per KV head.
 sa_status layer_fused_launch(const AttnLaunch& fa, const AttnLaunch& swa, const DeltaLaunch& kda, const DeltaLaunch& gdn,
-                             void* stream);
+                             PendingMerge* pending, void* stream);
+
+// Merges what `pending` holds in a launch of its own (no-op when empty) and empties it.
+sa_status layer_merge_flush(PendingMerge* pending, void* stream);
 
 }  // namespace sa

@@ -6,31 +6,53 @@
 // chip drains, and at small batches the ~6 us a dependent launch costs is most of the step.  Here the
 // workgroups of all four mixers form one grid, in the order FA ranges, SWA ranges, KDA tiles, GDN
 // tiles: the long attention ranges start first and the short recurrent tiles fill the slots they
-// free, so the read-modify-write of the states meets the K/V stream only at that boundary.  A second
-// small launch merges the partial results of both attention kinds (merging inside the first launch, by the
-// workgroup that finds all other page ranges finished, was measured: with full fences it doubles the step time,
-// with device-scope stores and loads it is no faster at batch 128 and slower at batch 8).  The bodies are the ones of the
-// stand-alone kernels (attn_device.h, delta_step_device.h); only the index arithmetic differs.
+// free, so the read-modify-write of the states meets the K/V stream only at that boundary.  The partial
+// results of the attention ranges are merged at the head of the NEXT layer's launch (layers write disjoint
+// outputs and the stream orders the launches), so a layer costs one launch; only the last fused layer of a
+// stack is followed by a small merge launch.  (Merging inside the same launch, by the workgroup that finds all
+// other page ranges finished, was measured: with full fences it doubles the step time, with device-scope stores
+// and loads it is no faster at batch 128 and slower at batch 8.)  The bodies are the ones of the stand-alone
+// kernels (attn_device.h, delta_step_device.h); only the index arithmetic differs.
 #include "layer_fused.h"
 
 #include "common.h"
 
 namespace {
 
+// Items of an earlier layer's attention calls to merge: [0, end_fa) of the full-attention call, the rest of the
+// sliding-window call; two items (128 threads each) per workgroup of 256.
+struct MergeParams {
+  sa::AttnParams fa, swa;
+  int end_fa, n_items;
+};
+
+__device__ __forceinline__ void merge_items(const MergeParams& m, int first_item) {
+  const int item = first_item + (threadIdx.x >> 7), d = threadIdx.x & 127;
+  if (item >= m.n_items) return;
+  if (item < m.end_fa)
+    attn_merge_body(m.fa, item, d);
+  else
+    attn_merge_body(m.swa, item - m.end_fa, d);
+}
+
 struct LayerParams {
+  MergeParams prev;
   sa::AttnParams fa, swa;
   sa::DeltaParams kda, gdn;
-  // prefix sums over the grid: [0, end_fa) FA, [end_fa, end_swa) SWA, [end_swa, end_kda) KDA, the rest GDN
-  int end_fa, end_swa, end_kda;
+  // prefix sums over the grid: [0, end_prev) merges of the earlier layer, [end_prev, end_fa) FA, [end_fa, end_swa) SWA,
+  // [end_swa, end_kda) KDA, the rest GDN
+  int end_prev, end_fa, end_swa, end_kda;
 };
 
 __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
   __shared__ AttnShared sm;
   const int id = blockIdx.x;
-  if (id < p.end_swa) {
+  if (id < p.end_prev) {
+    merge_items(p.prev, 2 * id);
+  } else if (id < p.end_swa) {
     const bool full = id < p.end_fa;
     const sa::AttnParams& a = full ? p.fa : p.swa;
-    const int i = full ? id : id - p.end_fa;
+    const int i = id - (full ? p.end_prev : p.end_fa);
     // KV head fastest, then page range, then request: the order of the stand-alone grid
     const int pairs = i / a.Hkv;
     attn_split_body<1>(a, i - pairs * a.Hkv, pairs % a.nsplit, pairs / a.nsplit, sm);
@@ -48,73 +70,92 @@ __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
 // A layer whose only mixers are the two recurrent ones: the same two tile bodies in one grid, without the
 // attention body's registers and LDS.
 struct RecurrentLayerParams {
+  MergeParams prev;
   sa::DeltaParams kda, gdn;
-  int end_kda;  // [0, end_kda) KDA tiles, the rest GDN tiles
+  int end_prev, end_kda;  // [0, end_prev) merges of the earlier layer, [end_prev, end_kda) KDA tiles, the rest GDN tiles
 };
 
 __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
-  const int id = interleaved_tile(blockIdx.x, gridDim.x);  // as the stand-alone step kernels visit their tiles
-  if (id < p.end_kda)
+  if (static_cast<int>(blockIdx.x) < p.end_prev) {
+    merge_items(p.prev, 2 * blockIdx.x);
+    return;
+  }
+  // as the stand-alone step kernels visit their tiles
+  const int id = interleaved_tile(static_cast<int>(blockIdx.x) - p.end_prev, static_cast<int>(gridDim.x) - p.end_prev);
+  const int n_kda = p.end_kda - p.end_prev;
+  if (id < n_kda)
     delta_step_body<128, 128, true, false>(p.kda, id, blockIdx.x);
   else
-    delta_step_body<128, 128, false, false>(p.gdn, id - p.end_kda, blockIdx.x);
+    delta_step_body<128, 128, false, false>(p.gdn, id - n_kda, blockIdx.x);
 }
 
-struct MergeParams {
-  sa::AttnParams fa, swa;
-  int end_fa;  // [0, end_fa) rows of the full-attention call, the rest of the sliding-window call
-};
+__global__ __launch_bounds__(256) void layer_merge_kernel(MergeParams p) { merge_items(p, 2 * blockIdx.x); }
 
-__global__ __launch_bounds__(128) void layer_merge_kernel(MergeParams p) {
-  const int id = blockIdx.x;
-  if (id < p.end_fa)
-    attn_merge_body(p.fa, id, threadIdx.x);
-  else
-    attn_merge_body(p.swa, id - p.end_fa, threadIdx.x);
+MergeParams merge_params(const sa::PendingMerge& pending) {
+  MergeParams m = {};
+  m.fa = pending.fa;
+  m.swa = pending.swa;
+  m.end_fa = pending.n_fa;
+  m.n_items = pending.n_fa + pending.n_swa;
+  return m;
 }
 
 }  // namespace
 
 sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch& swa, const sa::DeltaLaunch& kda,
-                                 const sa::DeltaLaunch& gdn, void* stream) {
+                                 const sa::DeltaLaunch& gdn, sa::PendingMerge* pending, void* stream) {
   const char* name = "placement_decode (fused layer)";
-  LayerParams p = {};
-  p.fa = fa.p;
-  p.swa = swa.p;
-  p.kda = kda.p;
-  p.gdn = gdn.p;
   const long long n_fa = fa.rows ? static_cast<long long>(fa.rows) * fa.p.Hkv * fa.p.nsplit : 0;
   const long long n_swa = swa.rows ? static_cast<long long>(swa.rows) * swa.p.Hkv * swa.p.nsplit : 0;
   const long long n_kda = kda.rows ? static_cast<long long>(kda.rows) * kda.p.H : 0;
   const long long n_gdn = gdn.rows ? static_cast<long long>(gdn.rows) * gdn.p.H : 0;
-  const long long total = n_fa + n_swa + n_kda + n_gdn;
-  SA_REQUIRE(total <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many workgroups in one layer", name);
-  if (total == 0) return SA_OK;
-  SA_REQUIRE((!fa.rows || fa.p.R <= 16) && (!swa.rows || swa.p.R <= 16), SA_EUNSUPPORTED, "%s: more than 16 query rows per KV head",
-             name);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (n_fa + n_swa == 0) {
-    RecurrentLayerParams rp;
-    rp.kda = kda.p;
-    rp.gdn = gdn.p;
-    rp.end_kda = static_cast<int>(n_kda);
-    sa::launch(SA_K_LAYER, layer_recurrent_kernel, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, rp);
-    return sa::check_launch(name);
-  }
+  const MergeParams prev = merge_params(*pending);
+  const long long n_prev = (prev.n_items + 1) / 2;
+  const long long total = n_prev + n_fa + n_swa + n_kda + n_gdn;
+  // what this layer leaves to be merged
   const long long m_fa = fa.rows && fa.p.nsplit > 1 ? static_cast<long long>(fa.rows) * fa.p.Hkv * fa.p.R : 0;
   const long long m_swa = swa.rows && swa.p.nsplit > 1 ? static_cast<long long>(swa.rows) * swa.p.Hkv * swa.p.R : 0;
-  SA_REQUIRE(m_fa + m_swa <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many rows to merge in one layer", name);
-  p.end_fa = static_cast<int>(n_fa);
-  p.end_swa = static_cast<int>(n_fa + n_swa);
-  p.end_kda = static_cast<int>(n_fa + n_swa + n_kda);
-  sa::launch(SA_K_LAYER, layer_decode_kernel, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
-  sa_status st = sa::check_launch(name);
-  if (st != SA_OK || m_fa + m_swa == 0) return st;
+  SA_REQUIRE(total <= 0x7fffffffLL && m_fa + m_swa <= 0x7ffffffeLL, SA_EUNSUPPORTED, "%s: too many workgroups in one layer", name);
+  SA_REQUIRE((!fa.rows || fa.p.R <= 16) && (!swa.rows || swa.p.R <= 16), SA_EUNSUPPORTED, "%s: more than 16 query rows per KV head",
+             name);
+  if (total == 0) return SA_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (n_fa + n_swa == 0) {
+    RecurrentLayerParams rp = {};
+    rp.prev = prev;
+    rp.kda = kda.p;
+    rp.gdn = gdn.p;
+    rp.end_prev = static_cast<int>(n_prev);
+    rp.end_kda = static_cast<int>(n_prev + n_kda);
+    sa::launch(SA_K_LAYER, layer_recurrent_kernel, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, rp);
+  } else {
+    LayerParams p = {};
+    p.prev = prev;
+    p.fa = fa.p;
+    p.swa = swa.p;
+    p.kda = kda.p;
+    p.gdn = gdn.p;
+    p.end_prev = static_cast<int>(n_prev);
+    p.end_fa = static_cast<int>(n_prev + n_fa);
+    p.end_swa = static_cast<int>(n_prev + n_fa + n_swa);
+    p.end_kda = static_cast<int>(n_prev + n_fa + n_swa + n_kda);
+    sa::launch(SA_K_LAYER, layer_decode_kernel, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
+  }
+  const sa_status st = sa::check_launch(name);
+  if (st != SA_OK) return st;
+  *pending = sa::PendingMerge();
+  if (m_fa) pending->fa = fa.p;
+  if (m_swa) pending->swa = swa.p;
+  pending->n_fa = static_cast<int>(m_fa);
+  pending->n_swa = static_cast<int>(m_swa);
+  return SA_OK;
+}
 
-  MergeParams m;
-  m.fa = fa.p;
-  m.swa = swa.p;
-  m.end_fa = static_cast<int>(m_fa);
-  sa::launch(SA_K_ATTN_MERGE, layer_merge_kernel, dim3(static_cast<unsigned>(m_fa + m_swa)), dim3(128), 0, s, m);
-  return sa::check_launch("placement_decode (fused merge)");
+sa_status sa::layer_merge_flush(sa::PendingMerge* pending, void* stream) {
+  const MergeParams m = merge_params(*pending);
+  *pending = sa::PendingMerge();
+  if (m.n_items == 0) return SA_OK;
+  sa::launch(SA_K_ATTN_MERGE, layer_merge_kernel, dim3(static_cast<unsigned>((m.n_items + 1) / 2)), dim3(256), 0,
+             static_cast<hipStream_t>(stream), m);
+  return sa::check_launch("placement_decode (merge of the last fused layer)");
 }

@@ -99,8 +99,9 @@ size_t align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
 
 }  // namespace
 
-// Full attention's partial results sit at the start of the workspace, the sliding window's behind them (a fused
-// layer launch has both in flight at once).
+// The workspace is two halves used by alternate layers: the partial results of a fused layer are merged by the
+// next layer's launch, which writes its own into the other half.  Within a half, full attention's partial results
+// sit at the start and the sliding window's behind them (a fused layer launch has both in flight at once).
 extern "C" size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* sh, int T, int max_seq_len, int window) {
   if (!plan || !sh) return 0;
   size_t need = 0;
@@ -110,11 +111,11 @@ extern "C" size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes
     const size_t ws = ns ? attn_decode_workspace_bytes(ns, T, sh->Hq, sh->Hkv, sh->D, max_seq_len, window) : 0;
     need = std::max(need, align_up(wf, 256) + ws);
   }
-  return need;
+  return 2 * align_up(need, 256);
 }
 
 extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* sh, int T, int window,
-                                      float attn_scale, float rec_scale, void* workspace, size_t workspace_bytes,
+                                      float attn_scale, float rec_scale, void* whole_workspace, size_t whole_workspace_bytes,
                                       void* stream) {
   const char* name = "placement_decode";
   SA_REQUIRE(plan && io && sh, SA_EINVAL, "%s: null plan, io or shapes", name);
@@ -122,17 +123,22 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
   SA_REQUIRE(static_cast<long long>(sh->H) * sh->dv == static_cast<long long>(sh->Hq) * sh->D, SA_EINVAL,
              "%s: H*dv must equal Hq*D so that all mixers share the output rows", name);
   const int B = plan->B;
+  SA_REQUIRE(sa::aligned(whole_workspace, 256), SA_EINVAL, "%s: the workspace must be aligned to 256 bytes", name);
+  const size_t half_bytes = whole_workspace_bytes / 2 / 256 * 256;
   const bool can_fuse = T == 1 && sh->dk == 128 && sh->dv == 128 && sh->Hkv >= 1 && sh->Hq / sh->Hkv <= 16;
   // Two passes over the stack: the first only checks every launch's arguments, so that a bad descriptor
   // anywhere is reported before anything has been enqueued.
   for (int pass = 0; pass < 2; ++pass) {
     const bool check = pass == 0;
+    sa::PendingMerge pending;  // partial results of the last fused layer, merged by the next launch
     for (int l = 0; l < plan->L; ++l) {
       const sa_layer_io& x = io[l];
       const int* cnt = &plan->counts[l * 4];
       const int32_t* lists[4];
       for (int m = 0; m < 4; ++m) lists[m] = plan->dev_lists + plan->offsets[l * 4 + m];
-      // where each attention kind keeps its partial results
+      // where each attention kind keeps its partial results: this layer's half of the workspace
+      void* const workspace = whole_workspace ? static_cast<char*>(whole_workspace) + (l & 1) * half_bytes : nullptr;
+      const size_t workspace_bytes = half_bytes;
       const size_t need_fa = cnt[0] ? attn_decode_workspace_bytes(cnt[0], T, sh->Hq, sh->Hkv, sh->D, x.max_seq_len, 0) : 0;
       const size_t off_swa = std::min(align_up(need_fa, 256), workspace_bytes);
       char* ws_swa = workspace ? static_cast<char*>(workspace) + off_swa : nullptr;
@@ -160,9 +166,13 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
           st = sa::delta_prepare(false, x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, lists[3], cnt[3], B,
                                  T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, nullptr, &gdn);
         if (st != SA_OK) return st;
-        if (!check) st = sa::layer_fused_launch(fa, swa, kda, gdn, stream);
+        if (!check) st = sa::layer_fused_launch(fa, swa, kda, gdn, &pending, stream);
         if (st != SA_OK) return st;
         continue;
+      }
+      if (!check) {
+        const sa_status st = sa::layer_merge_flush(&pending, stream);
+        if (st != SA_OK) return st;
       }
 
       for (int m = 0; m < 4; ++m) {
@@ -199,6 +209,10 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
         }
         if (st != SA_OK) return st;
       }
+    }
+    if (!check) {
+      const sa_status st = sa::layer_merge_flush(&pending, stream);
+      if (st != SA_OK) return st;
     }
   }
   return SA_OK;

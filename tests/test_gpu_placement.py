@@ -185,6 +185,31 @@ def test_verify_pass_then_commit_of_accepted_prefixes(T):
                     assert np.array_equal(states[l][r], layers[l]["state"][r]), (l, r, m)
 
 
+@pytest.mark.parametrize("placements", [
+    ["FKF", "SGS"],            # fused (FA + SWA) -> fused recurrent-only layer, which merges layer 0 -> fused, last layer
+    ["FFKF", "KFGF", "SFKF"],  # fused -> a single-mixer layer (stand-alone launches) -> recurrent-only -> single mixer
+    ["FF", "SF", "KF"],        # fused -> single mixer
+    ["FFFF", "SSSS"],          # four fused layers in a row with both attention kinds: the workspace halves alternate
+])
+def test_partial_results_merged_by_the_next_layers_launch(placements):
+    """A fused layer leaves the merge of its attention ranges to the launch of the layer after it, whatever that
+    layer runs; the window is long enough for the sliding-window calls to split into ranges as well."""
+    L, B, ctx, window, max_pages = len(placements[0]), 7, 2100, 1100, 136
+    pid = (np.arange(B) % len(placements)).astype(np.int32)
+    lens = [2100, 1, 333, 2099, 1200, 16, 1999]
+    layers = build_stack(5600 + L, L, B, 1, ctx, max_pages, lens)
+    outs, states = run_stack(placements, pid, layers, 1, window, ctx, max_pages)
+    ref_outs, ref_states = om.placement_decode(placements, pid, layers, window, D ** -0.5, DK ** -0.5)
+    for l in range(L):
+        for r in range(B):
+            m = placements[pid[r]][l]
+            assert rel_err(outs[l][r], ref_outs[l][r]) <= OUT_TOL, (l, r, m)
+            if m in "KG":
+                assert rel_err(states[l][r], ref_states[l][r]) <= STATE_TOL, (l, r, m)
+            else:
+                assert np.array_equal(states[l][r], layers[l]["state"][r]), (l, r, m)
+
+
 @pytest.mark.parametrize("case", range(8))
 def test_random_stacks(case):
     """Seeded random stacks: number of layers, batch, placements, mixers per layer, ragged lengths, window, token
