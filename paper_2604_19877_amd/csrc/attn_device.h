@@ -311,22 +311,43 @@ __device__ __forceinline__ void attn_split_body(const AttnParams& p, const int g
 }
 
 // One thread per output element of a (request, KV head, query row): combine the nsplit partials in index
-// order and normalise.
+// order and normalise.  The partials are fetched eight ranges at a time (sixteen independent loads in flight, not
+// one after the other) and folded into a running maximum, normaliser and sum by the online-softmax rule.
 // `item` = (r * Hkv + g) * R + row; d = the output dimension this thread owns.
 __device__ __forceinline__ void attn_merge_body(const AttnParams& p, const int item, const int d) {
+  constexpr int kBatch = 8;
   const int row = item % p.R;
   const int g = (item / p.R) % p.Hkv;
   const int r = item / (p.R * p.Hkv);
   const int b = p.req_idx ? p.req_idx[r] : r;
   const size_t part0 = (static_cast<size_t>(r) * p.Hkv + g) * p.nsplit * p.R + row;
-  float m = kNegBig;
-  for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, p.part_ml[part0 + static_cast<size_t>(s) * p.R].x);
-  float l = 0.f, acc = 0.f;
-  for (int s = 0; s < p.nsplit; ++s) {
-    const float2 ml = p.part_ml[part0 + static_cast<size_t>(s) * p.R];
-    const float f = exp2f(ml.x - m);
-    l = fmaf(ml.y, f, l);
-    acc = fmaf(p.part_o[(part0 + static_cast<size_t>(s) * p.R) * kD + d], f, acc);
+  const float2* const ml = p.part_ml + part0;         // range s at ml[s * R]
+  const float* const po = p.part_o + part0 * kD + d;  // range s at po[s * R * kD]
+  float m = kNegBig, l = 0.f, acc = 0.f;
+  for (int s0 = 0; s0 < p.nsplit; s0 += kBatch) {
+    float2 mlv[kBatch];
+    float ov[kBatch];
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const size_t s = static_cast<size_t>(min(s0 + j, p.nsplit - 1));  // past the end: the last range again, left out below
+      mlv[j] = ml[s * p.R];
+      ov[j] = po[s * p.R * kD];
+    }
+    float m_new = m;
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      if (s0 + j < p.nsplit) m_new = fmaxf(m_new, mlv[j].x);
+    const float keep = exp2f(m - m_new);
+    l *= keep;
+    acc *= keep;
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      if (s0 + j < p.nsplit) {
+        const float f = exp2f(mlv[j].x - m_new);
+        l = fmaf(mlv[j].y, f, l);
+        acc = fmaf(ov[j], f, acc);
+      }
+    m = m_new;
   }
   const int t = row / p.G, hq = g * p.G + row % p.G;
   p.out[((static_cast<size_t>(b) * p.T + t) * p.Hq + hq) * kD + d] = l > 0.f ? acc / l : 0.f;
