@@ -5,8 +5,8 @@
 // state; its scheduler still batches same-placement requests together.  Here a batch may mix
 // placements freely: a plan groups the requests per (layer, mixer) once, and every kernel takes
 // the group's request list as an indirection.  A one-token decode step at 128x128 states runs every layer
-// that mixes mixers as one fused launch (plus one merge launch); a layer with a single mixer present, and any
-// multi-token step, runs the stand-alone kernel of each mixer present.
+// as one fused launch, whose head also merges the attention partial results of the layer before; any
+// multi-token step runs the stand-alone kernel of each mixer present.
 #include <cstring>
 #include <vector>
 
@@ -143,11 +143,11 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
       const size_t off_swa = std::min(align_up(need_fa, 256), workspace_bytes);
       char* ws_swa = workspace ? static_cast<char*>(workspace) + off_swa : nullptr;
       const size_t ws_swa_bytes = workspace_bytes - off_swa;
-      const int present = (cnt[0] > 0) + (cnt[1] > 0) + (cnt[2] > 0) + (cnt[3] > 0);
-
-      // One fused launch when the layer mixes mixers (measured from batch 8 / 2048-token contexts to batch 128 /
-      // 16384: 26 % to 0 % faster than one launch per mixer).
-      if (can_fuse && present >= 2 && !x.n_commit_rows) {
+      // One fused launch per layer (measured from batch 8 / 2048-token contexts to batch 128 / 16384: 26 % to 0 %
+      // faster than one launch per mixer).  A layer with a single mixer present runs the same body as the mixer's
+      // stand-alone kernel, but leaves its merge to the next launch (a single sequence through 48 layers: 15-20 %
+      // faster per step).
+      if (can_fuse && !x.n_commit_rows) {
         sa::AttnLaunch fa = {}, swa = {};
         sa::DeltaLaunch kda = {}, gdn = {};
         sa_status st = SA_OK;
