@@ -262,11 +262,11 @@ int placement_plan_count(const sa_plan* plan, int layer, char mixer);
  * because a fused layer's partial results are merged by the launch of the layer after it. */
 size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, int T, int max_seq_len, int window);
 /* io: host array of L descriptors.  Checks the arguments of every launch of the stack first (nothing is
- * enqueued if any is bad), then enqueues layer by layer.  A one-token step (T == 1) at 128x128 states with at most
- * 16 query heads per KV head runs every layer as one fused launch over the request lists of all mixers present; if
- * one of its attention calls has several page ranges, their partial results are merged at the head of the next
- * layer's launch (a small merge launch of its own follows the last layer, or a layer whose successor is not
- * fused).  Any other step, and a layer with n_commit_rows, runs one launch (attention: plus a merge) per mixer present.  Results do not depend on which of
+ * enqueued if any is bad), then enqueues layer by layer.  A step of T <= 4 tokens at 128x128 states with at most
+ * 16 query rows (T * Hq/Hkv) per KV head runs every layer as one fused launch over the request lists of all mixers
+ * present; if one of its attention calls has several page ranges, their partial results are merged at the head of
+ * the next layer's launch (a small merge launch of its own follows the last layer).  Any other step runs one launch
+ * (attention: plus a merge) per mixer present.  Results do not depend on which of
  * the two is taken, and every layer's output is complete in stream order when the call's last launch has run.
  * Recurrent layers update their states in place, by all T steps or by each request's n_commit_rows.
  * workspace: device memory, 256-byte aligned, at least placement_workspace_bytes(); SA_EWORKSPACE if too small. */

@@ -15,8 +15,8 @@ struct PendingMerge {
 // Enqueues one kernel that first merges what `pending` holds (the partial results of an earlier layer) and then
 // runs the prepared launches of this layer (any of them may have rows == 0).  On return `pending` describes this
 // layer's own partial results, to be merged by the next layer's launch or by layer_merge_flush: the buffers it
-// points to must not be written before that.  All four launches must be single-token decode calls (T == 1) at
-// 128x128 states and at most 16 query rows per KV head.
+// points to must not be written before that.  All four launches must be calls of at most 4 tokens at 128x128 states
+// and at most 16 query rows per KV head.
 sa_status layer_fused_launch(const AttnLaunch& fa, const AttnLaunch& swa, const DeltaLaunch& kda, const DeltaLaunch& gdn,
                              PendingMerge* pending, void* stream);
 

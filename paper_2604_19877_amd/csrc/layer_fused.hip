@@ -44,6 +44,9 @@ struct LayerParams {
   int end_prev, end_fa, end_swa, end_kda;
 };
 
+// MULTI: the recurrent calls run several tokens or a per-request committed prefix (a verify pass) on the
+// register-resident multi-token body; otherwise the one-token body of the decode hot path.
+template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
   __shared__ AttnShared sm;
   const int id = blockIdx.x;
@@ -61,9 +64,9 @@ __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
     const int tile = interleaved_tile(id - p.end_swa, static_cast<int>(gridDim.x) - p.end_swa);
     const int n_kda = p.end_kda - p.end_swa;
     if (tile < n_kda)
-      delta_step_body<128, 128, true, false>(p.kda, tile, blockIdx.x);
+      delta_step_body<128, 128, true, MULTI>(p.kda, tile, blockIdx.x);
     else
-      delta_step_body<128, 128, false, false>(p.gdn, tile - n_kda, blockIdx.x);
+      delta_step_body<128, 128, false, MULTI>(p.gdn, tile - n_kda, blockIdx.x);
   }
 }
 
@@ -75,6 +78,7 @@ struct RecurrentLayerParams {
   int end_prev, end_kda;  // [0, end_prev) merges of the earlier layer, [end_prev, end_kda) KDA tiles, the rest GDN tiles
 };
 
+template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
   if (static_cast<int>(blockIdx.x) < p.end_prev) {
     merge_items(p.prev, 2 * blockIdx.x);
@@ -84,9 +88,9 @@ __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerPara
   const int id = interleaved_tile(static_cast<int>(blockIdx.x) - p.end_prev, static_cast<int>(gridDim.x) - p.end_prev);
   const int n_kda = p.end_kda - p.end_prev;
   if (id < n_kda)
-    delta_step_body<128, 128, true, false>(p.kda, id, blockIdx.x);
+    delta_step_body<128, 128, true, MULTI>(p.kda, id, blockIdx.x);
   else
-    delta_step_body<128, 128, false, false>(p.gdn, id - n_kda, blockIdx.x);
+    delta_step_body<128, 128, false, MULTI>(p.gdn, id - n_kda, blockIdx.x);
 }
 
 __global__ __launch_bounds__(256) void layer_merge_kernel(MergeParams p) { merge_items(p, 2 * blockIdx.x); }
@@ -119,6 +123,9 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
   SA_REQUIRE((!fa.rows || fa.p.R <= 16) && (!swa.rows || swa.p.R <= 16), SA_EUNSUPPORTED, "%s: more than 16 query rows per KV head",
              name);
   if (total == 0) return SA_OK;
+  const auto needs_multi = [](const sa::DeltaLaunch& l) { return l.rows && (l.p.T != 1 || l.p.n_commit != 1 || l.p.n_commit_rows); };
+  const bool multi = needs_multi(kda) || needs_multi(gdn);
+  SA_REQUIRE(!kda.chunked && !gdn.chunked, SA_EUNSUPPORTED, "%s: calls of 5 and more tokens run on kernels of their own", name);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (n_fa + n_swa == 0) {
     RecurrentLayerParams rp = {};
@@ -127,7 +134,10 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
     rp.gdn = gdn.p;
     rp.end_prev = static_cast<int>(n_prev);
     rp.end_kda = static_cast<int>(n_prev + n_kda);
-    sa::launch(SA_K_LAYER, layer_recurrent_kernel, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, rp);
+    if (multi)
+      sa::launch(SA_K_LAYER, layer_recurrent_kernel<true>, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, rp);
+    else
+      sa::launch(SA_K_LAYER, layer_recurrent_kernel<false>, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, rp);
   } else {
     LayerParams p = {};
     p.prev = prev;
@@ -139,7 +149,10 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
     p.end_fa = static_cast<int>(n_prev + n_fa);
     p.end_swa = static_cast<int>(n_prev + n_fa + n_swa);
     p.end_kda = static_cast<int>(n_prev + n_fa + n_swa + n_kda);
-    sa::launch(SA_K_LAYER, layer_decode_kernel, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
+    if (multi)
+      sa::launch(SA_K_LAYER, layer_decode_kernel<true>, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
+    else
+      sa::launch(SA_K_LAYER, layer_decode_kernel<false>, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
   }
   const sa_status st = sa::check_launch(name);
   if (st != SA_OK) return st;

@@ -4,9 +4,9 @@
 // i.e. one mixer per layer, and dispatches inside the layer on that name with no global mutable
 // state; its scheduler still batches same-placement requests together.  Here a batch may mix
 // placements freely: a plan groups the requests per (layer, mixer) once, and every kernel takes
-// the group's request list as an indirection.  A one-token decode step at 128x128 states runs every layer
-// as one fused launch, whose head also merges the attention partial results of the layer before; any
-// multi-token step runs the stand-alone kernel of each mixer present.
+// the group's request list as an indirection.  A step of up to 4 tokens at 128x128 states runs every layer
+// as one fused launch, whose head also merges the attention partial results of the layer before; a longer
+// step runs the stand-alone kernel of each mixer present.
 #include <cstring>
 #include <vector>
 
@@ -125,7 +125,8 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
   const int B = plan->B;
   SA_REQUIRE(sa::aligned(whole_workspace, 256), SA_EINVAL, "%s: the workspace must be aligned to 256 bytes", name);
   const size_t half_bytes = whole_workspace_bytes / 2 / 256 * 256;
-  const bool can_fuse = T == 1 && sh->dk == 128 && sh->dv == 128 && sh->Hkv >= 1 && sh->Hq / sh->Hkv <= 16;
+  // up to 4 tokens per call: the recurrent mixers stay on the register-resident kernel and the query rows of a KV head fit one tile
+  const bool can_fuse = T >= 1 && T <= 4 && sh->dk == 128 && sh->dv == 128 && sh->Hkv >= 1 && T * (sh->Hq / sh->Hkv) <= 16;
   // Two passes over the stack: the first only checks every launch's arguments, so that a bad descriptor
   // anywhere is reported before anything has been enqueued.
   for (int pass = 0; pass < 2; ++pass) {
@@ -147,7 +148,7 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
       // faster than one launch per mixer).  A layer with a single mixer present runs the same body as the mixer's
       // stand-alone kernel, but leaves its merge to the next launch (a single sequence through 48 layers: 15-20 %
       // faster per step).
-      if (can_fuse && !x.n_commit_rows) {
+      if (can_fuse) {
         sa::AttnLaunch fa = {}, swa = {};
         sa::DeltaLaunch kda = {}, gdn = {};
         sa_status st = SA_OK;
@@ -161,10 +162,10 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
                                 &swa);
         if (st == SA_OK && cnt[2])
           st = sa::delta_prepare(true, x.q, x.k, x.v, x.alpha_vec, x.beta, x.state, x.state, x.out, x.slot_idx, lists[2], cnt[2], B, T,
-                                 sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, nullptr, &kda);
+                                 sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, x.n_commit_rows, &kda);
         if (st == SA_OK && cnt[3])
           st = sa::delta_prepare(false, x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, lists[3], cnt[3], B,
-                                 T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, nullptr, &gdn);
+                                 T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, x.n_commit_rows, &gdn);
         if (st != SA_OK) return st;
         if (!check) st = sa::layer_fused_launch(fa, swa, kda, gdn, &pending, stream);
         if (st != SA_OK) return st;
