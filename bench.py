@@ -578,11 +578,26 @@ def small_stack_graph(torch, steps=20, warmup=3):
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - t0) * 1e3 / steps
         nbytes = w.algorithmic_bytes()
-        return {"workload": "48-layer mixers-only stack, batch 8, contexts 2048, window 1024, 3 placements",
-                "eager_ms_per_step": round(eager_ms, 3), "graph_ms_per_step": round(graph_ms, 3), "alg_bytes": nbytes,
-                "graph_frac_hbm_peak": round(nbytes / (graph_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        res = {"workload": "48-layer mixers-only stack, batch 8, contexts 2048, window 1024, 3 placements",
+               "eager_ms_per_step": round(eager_ms, 3), "graph_ms_per_step": round(graph_ms, 3), "alg_bytes": nbytes,
+               "graph_frac_hbm_peak": round(nbytes / (graph_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     finally:
         w.close()
+    # the same stack as a verify pass over 4 drafted tokens per request
+    w = PlacementWorkload(B=8, L=48, ctx=2048, window=1024, T=4, seed=5100)
+    try:
+        s = torch.cuda.current_stream()
+        for _ in range(warmup):
+            w.step(s)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            w.step(s)
+        torch.cuda.synchronize()
+        res["verify_T4_eager_ms_per_pass"] = round((time.perf_counter() - t0) * 1e3 / steps, 3)
+    finally:
+        w.close()
+    return res
 
 
 def cpu_baseline(np, torch, gen, rec, q_h, kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale, attn_scale):
