@@ -266,8 +266,11 @@ size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, i
  * 16 query rows (T * Hq/Hkv) per KV head runs every layer as one fused launch over the request lists of all mixers
  * present; if one of its attention calls has several page ranges, their partial results are merged at the head of
  * the next layer's launch (a small merge launch of its own follows the last layer).  Any other step runs one launch
- * (attention: plus a merge) per mixer present.  Results do not depend on which of
- * the two is taken, and every layer's output is complete in stream order when the call's last launch has run.
+ * (attention: plus a merge) per mixer present.  Either way the attention rows
+ * come out bit for bit as from attn_decode over the same request list; recurrent rows agree with the stand-alone
+ * steps to the rounding order of their sums (a tile's rows are added in an order that depends on the workgroup's place
+ * in the grid; a given launch is run-to-run deterministic).  Every layer's output is complete in stream order when
+ * the call's last launch has run.
  * Recurrent layers update their states in place, by all T steps or by each request's n_commit_rows.
  * workspace: device memory, 256-byte aligned, at least placement_workspace_bytes(); SA_EWORKSPACE if too small. */
 sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,

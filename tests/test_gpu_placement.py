@@ -210,6 +210,49 @@ def test_partial_results_merged_by_the_next_layers_launch(placements):
                 assert np.array_equal(states[l][r], layers[l]["state"][r]), (l, r, m)
 
 
+@pytest.mark.parametrize("T", [1, 4])
+def test_fused_layers_against_the_stand_alone_entry_points(T):
+    """The fused per-layer launches run the bodies of the stand-alone kernels over the same request lists and page
+    ranges: attention rows must come out bit for bit as from attn_decode; a recurrent tile sums its rows in an order
+    that depends on where its workgroup sits in the grid, so those rows agree to rounding only."""
+    L, B, ctx, window, max_pages = 3, 7, 2100, 1100, 136
+    placements = ["FKS", "SGF", "KFG", "GSK"]
+    pid = (np.arange(B) % 4).astype(np.int32)
+    lens = [2100, T, 333, 2099, 1200, 16, 1999]
+    layers = build_stack(5700 + T, L, B, T, ctx, max_pages, lens)
+    outs, states = run_stack(placements, pid, layers, T, window, ctx, max_pages)
+    for l, io in enumerate(layers):
+        kphys, vphys = kl.to_physical(io["kpool"], io["vpool"])
+        t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
+        kd, vd = dev(kphys), dev(vphys)
+        state = dev(io["state"].copy())
+        out = torch.full((B, T, H, DV), 55.0, dtype=torch.float32, device="cuda")
+        for m in "FSKG":
+            req = np.array([r for r in range(B) if placements[pid[r]][l] == m], dtype=np.int32)
+            if len(req) == 0:
+                continue
+            if m in "FS":
+                w = 0 if m == "F" else window
+                ws_bytes = sa.attn_decode_workspace_bytes(len(req), T, HQ, HKV, D, ctx, w)
+                ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+                sa.attn_decode(t["qa"], kd, vd, io["n_pages"], t["page_table"], max_pages, t["seq_lens"], dev(req), len(req), out,
+                               B, T, HQ, HKV, D, 16, ctx, w, D ** -0.5, ws, ws_bytes)
+            else:
+                fn = sa.kda_decode_step if m == "K" else sa.gdn_decode_step
+                alpha = t["alpha_vec"] if m == "K" else t["alpha_scalar"]
+                fn(t["q"], t["k"], t["v"], alpha, t["beta"], state, state, out, None, dev(req), len(req), B, T, H, H, DK, DV,
+                   DK ** -0.5, T)
+        torch.cuda.synchronize()
+        alone_o, alone_s = host(out), host(state)
+        for r in range(B):
+            if placements[pid[r]][l] in "FS":
+                assert np.array_equal(outs[l][r], alone_o[r]), (l, r)
+                assert np.array_equal(states[l][r], alone_s[r]), (l, r)
+            else:
+                assert rel_err(outs[l][r], alone_o[r]) <= 2e-6, (l, r)
+                assert rel_err(states[l][r], alone_s[r]) <= 2e-6, (l, r)
+
+
 @pytest.mark.parametrize("case", range(8))
 def test_random_stacks(case):
     """Seeded random stacks: number of layers, batch, placements, mixers per layer, ragged lengths, window, token
