@@ -14,9 +14,10 @@ from test_gpu_placement import D, DK, DV, H, HKV, HQ, build_stack
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("T", [1, 8])
+@pytest.mark.parametrize("T", [1, 4, 8])
 def test_placement_step_replays_from_a_graph(T):
-    """T = 8 is a verify pass: two query tiles in attention, the chunk-parallel kernels for the recurrent mixers."""
+    """T = 4 is a verify pass on the fused per-layer launches (partial results merged by the next layer's launch);
+    T = 8 a longer one: two query tiles in attention, the chunk-parallel kernels for the recurrent mixers."""
     L, B, ctx, window, max_pages = 8, 6, 700, 128, 48
     placements = [gen.placement_string(8001 + i, L) for i in range(3)]
     pid = np.arange(B, dtype=np.int32) % 3
