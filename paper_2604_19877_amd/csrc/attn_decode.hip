@@ -13,14 +13,14 @@
 // Matrix-core mapping.  The Hq/Hkv query heads that share a KV head (times the T new tokens) form up
 // to 16 query rows, which is one MFMA N-tile:
 //   scores   S^T[token][row] = K[token][:] . Q[row][:]      4 x mfma_f32_16x16x32_bf16 per page
-//   output   O^T[dim][row]  += V^T[dim][token] P^T[token][row]   8 x 2 x mfma_f32_16x16x16_bf16
+//   output   O^T[dim][row]  += V^T[dim][token] P^T[token][row]   8 x mfma_f32_16x16x32_bf16 (both terms of P at once)
 // The in-page K and V layouts (see the header) are exactly the A-operand register layouts of those
 // two instructions, so lane l loads its fragment from `block + i*stride + l*width`: no LDS staging,
 // no transposes.  S^T leaves the matrix core with lane (row = l%16, group = l/16) holding tokens
 // 4*group..4*group+3 of its row, which is also the B-operand layout of the second product, and O^T
 // keeps that same row in the lane, so the whole online softmax is lane-local except for a 2-step
 // maximum over the 4 token groups.  Probabilities are split into two bf16 terms (p = hi + lo) so the
-// second product carries ~16 mantissa bits of p instead of 8.
+// second product carries ~16 mantissa bits of p instead of 8; its 32-wide contraction runs over (token, term).
 #include "attn_device.h"
 #include "common.h"
 

@@ -244,8 +244,10 @@ __device__ __forceinline__ void attn_split_body(const AttnParams& p, const int g
         hi.y = pack_bf16_rne(pv[2], pv[3]);
         lo.x = pack_bf16_rne(pv[0] - __uint_as_float(hi.x << 16), pv[1] - __uint_as_float(hi.x & 0xffff0000u));
         lo.y = pack_bf16_rne(pv[2] - __uint_as_float(hi.y << 16), pv[3] - __uint_as_float(hi.y & 0xffff0000u));
-        const s16x4 p_hi = __builtin_bit_cast(s16x4, hi);
-        const s16x4 p_lo = __builtin_bit_cast(s16x4, lo);
+        // Both terms of P in one 16x16x32 product: its contraction index runs over (token, term), slots 0-3 of a
+        // lane's 8 holding tokens 4*grp..+3 with the first term and slots 4-7 the same tokens with the second, so
+        // the V operand is the lane's 4 values twice.
+        const bf16x8 p_two = __builtin_bit_cast(bf16x8, uint4{hi.x, hi.y, lo.x, lo.y});
 
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) {
@@ -254,10 +256,8 @@ __device__ __forceinline__ void attn_split_body(const AttnParams& p, const int g
           acc[1] *= corr;
           acc[2] *= corr;
           acc[3] *= corr;
-          const s16x4 vf = __builtin_bit_cast(s16x4, cur.v[nb]);
-          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, p_hi, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, p_lo, acc, 0, 0, 0);
-          o[n][nb] = acc;
+          const bf16x8 v_twice = __builtin_bit_cast(bf16x8, uint4{cur.v[nb].x, cur.v[nb].y, cur.v[nb].x, cur.v[nb].y});
+          o[n][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_twice, p_two, acc, 0, 0, 0);
         }
       }
       cur = nxt;
