@@ -101,13 +101,6 @@ __device__ __forceinline__ float row_shr(float x) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x110 + D, 0xf, 0xf, true));
 }
 
-// Orders this wavefront's LDS writes before its later LDS reads by other lanes.
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Forward substitution (I + A) delta = rhs for this wavefront's 2 x 16 columns, rows 4 to a lane.
 // a_off holds A with the 4x4 diagonal blocks zeroed ([16][kMatRow]), a_dia those blocks ([16][4]).
 // Stage gp: the lanes of row group gp finish their 4 rows (the other groups run the same code with zero

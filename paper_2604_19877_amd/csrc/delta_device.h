@@ -40,18 +40,20 @@ __device__ __forceinline__ float load_uniform(const float* p, size_t i) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// Sum over the 8 lanes that share c8 (lane bits 3..5).  Lane l ^ 8 sits in the same row of 16 lanes: with ROW_ROTATE a
-// row rotation by 8 (one DPP-modified add) fetches it without a trip through the LDS crossbar (measured per kernel:
-// the multi-token KDA step is faster with three shuffles).
-template <bool ROW_ROTATE = true>
+// Sum over the 8 lanes that share c8 (lane bits 3..5).  Lane l ^ 8 sits in the same row of 16 lanes: a row rotation
+// by 8 (one DPP-modified add) fetches it without a trip through the LDS crossbar.
 __device__ __forceinline__ float reduce_r8(float x) {
-  if constexpr (ROW_ROTATE)
-    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
-  else
-    x += __shfl_xor(x, 8);
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
   x += __shfl_xor(x, 16);
   x += __shfl_xor(x, 32);
   return x;
+}
+
+// Orders this wavefront's LDS writes before its later LDS reads by other lanes (no other wavefront involved).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 }  // namespace

@@ -109,7 +109,6 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   const int c8 = lane & 7, r8 = lane >> 3;
   const int row0 = r8 * RPL;
   const int col0 = wave * 32 + c8 * 4;
-  constexpr bool ROTATE = !(KDA && MULTI);
   constexpr bool LAZY = MULTI && !KDA;  // GDN over several tokens: the scalar decay is carried as a common factor
   float carry = 1.f;
   const int T = MULTI ? p.T : 1;
@@ -125,13 +124,47 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   // scheduling barrier keeps the compiler from sinking any of them towards its first use, which
   // would put a full memory latency on the critical path of every tile.
   StepOperands<RPL> cur, nxt;
-  float4 gate_vec[RPL / 4];  // KDA only: single-buffered, the next step's is requested as soon as this step's is applied
+  float4 gate_vec[RPL / 4];  // KDA, one token per call: this lane's gates straight from memory
   load_operands<DK, DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0, turn);
-  if constexpr (KDA) load_gate_vector<DK>(gate_vec, p, static_cast<size_t>(b) * T, h, row0, turn);
+  // KDA over several tokens: every wavefront fetches the gate vectors of all its steps once, coalesced (DK floats per
+  // step), and parks them in a region of LDS of its own; a step then reads its lane's rows from there.  Per-lane
+  // global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row), as many load
+  // instructions per 4 steps as the state tile itself takes.  No other wavefront reads the region: no barrier.
+  constexpr int kGateSteps = DK == 128 ? 4 : 16;  // longer calls at 128x128 run on the chunk-parallel kernels
+  constexpr bool kGatesInLds = KDA && MULTI;
+  __shared__ float gate_lds[kGatesInLds ? (DV / 32) * kGateSteps * DK : 1];
+  float* const my_gates = gate_lds + (kGatesInLds ? wave * kGateSteps * DK : 0);
+  float2 gate_fetch[kGatesInLds ? kGateSteps : 1];
+  if constexpr (kGatesInLds) {
+    const float* const src = p.alpha + (static_cast<size_t>(b) * T * p.H + h) * DK;
+#pragma unroll
+    for (int t = 0; t < kGateSteps; ++t) {
+      if (t < T) {
+        if constexpr (DK == 128)
+          gate_fetch[t] = *reinterpret_cast<const float2*>(src + static_cast<size_t>(t) * p.H * DK + 2 * lane);
+        else
+          gate_fetch[t].x = src[static_cast<size_t>(t) * p.H * DK + lane];
+      }
+    }
+  } else if constexpr (KDA) {
+    load_gate_vector<DK>(gate_vec, p, static_cast<size_t>(b) * T, h, row0, turn);
+  }
   float4 s[RPL];
 #pragma unroll
   for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + 4 * turn) & (RPL - 1)) * DV);
   __builtin_amdgcn_sched_barrier(0);
+  if constexpr (kGatesInLds) {
+#pragma unroll
+    for (int t = 0; t < kGateSteps; ++t) {
+      if (t < T) {
+        if constexpr (DK == 128)
+          *reinterpret_cast<float2*>(my_gates + t * DK + 2 * lane) = gate_fetch[t];
+        else
+          my_gates[t * DK + lane] = gate_fetch[t].x;
+      }
+    }
+    wave_lds_sync();
+  }
 
   if (MULTI && n_commit == 0 && p.state_out != p.state_in) {
 #pragma unroll
@@ -152,7 +185,8 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
     if constexpr (KDA) {
 #pragma unroll
       for (int i = 0; i < RPL / 4; ++i) {
-        const float4 a = gate_vec[i];
+        const float4 a = kGatesInLds ? *reinterpret_cast<const float4*>(my_gates + t * DK + row0 + 4 * ((i + turn) & (RPL / 4 - 1)))
+                                     : gate_vec[i];
         const float av[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -162,9 +196,6 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
           x.z *= av[e];
           x.w *= av[e];
         }
-      }
-      if constexpr (MULTI) {
-        if (t + 1 < T) load_gate_vector<DK>(gate_vec, p, bt + 1, h, row0, turn);
       }
     } else if constexpr (MULTI) {
       // The registers hold the state divided by `carry`, the product of the gates since the last time it was
@@ -207,15 +238,15 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
       w.w = fmaf(s[m].w, qf[m], w.w);
       kq = fmaf(kf[m], qf[m], kq);
     }
-    u.x = reduce_r8<ROTATE>(u.x);
-    u.y = reduce_r8<ROTATE>(u.y);
-    u.z = reduce_r8<ROTATE>(u.z);
-    u.w = reduce_r8<ROTATE>(u.w);
-    w.x = reduce_r8<ROTATE>(w.x);
-    w.y = reduce_r8<ROTATE>(w.y);
-    w.z = reduce_r8<ROTATE>(w.z);
-    w.w = reduce_r8<ROTATE>(w.w);
-    kq = reduce_r8<ROTATE>(kq);
+    u.x = reduce_r8(u.x);
+    u.y = reduce_r8(u.y);
+    u.z = reduce_r8(u.z);
+    u.w = reduce_r8(u.w);
+    w.x = reduce_r8(w.x);
+    w.y = reduce_r8(w.y);
+    w.z = reduce_r8(w.z);
+    w.w = reduce_r8(w.w);
+    kq = reduce_r8(kq);
 
     if constexpr (LAZY) {
       u.x *= carry;
