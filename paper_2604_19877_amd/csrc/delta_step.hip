@@ -23,7 +23,10 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
   delta_step_body<DK, DV, KDA, MULTI>(p, interleaved_tile(blockIdx.x, gridDim.x), blockIdx.x);
 }
 
-constexpr int kChunkedFrom = 5;  // tokens per call from which the decode steps run on the chunk-parallel kernels
+// Tokens per call from which the decode steps run on the chunk-parallel kernels (measured at batch 64: GDN 5 tokens
+// 53.2 us on the register-resident kernel against 54.2 us chunked, 6 tokens 54.2 against 53.4; KDA 5 tokens 53.6 against
+// 59.7 us, 6 tokens 56.1 against 59.0, 8 tokens 62.6 against 59.8).  The register-resident kernel holds room for 6 steps.
+constexpr int kChunkedFromGdn = 5, kChunkedFromKda = 7;
 
 }  // namespace
 
@@ -51,9 +54,8 @@ sa_status sa::delta_prepare(bool kda, const void* q, const void* k, const void* 
                  sa::aligned(beta, 4) && sa::aligned(slot_idx, 4) && sa::aligned(req_idx, 4) && sa::aligned(n_commit_rows, 4),
              SA_EINVAL, "%s: misaligned pointer", name);
   SA_REQUIRE(static_cast<long long>(rows) * H <= 0x7fffffffLL, SA_EUNSUPPORTED, "%s: too many tiles", name);
-  // From 5 tokens per call the chunk-parallel kernels are faster at 128x128 (8 tokens: 56 / 62 us against
-  // 66 / 74 us); they take the same arguments and write the same state for any n_commit.
-  if (dk == 128 && T >= kChunkedFrom) {
+  // Longer calls run on the chunk-parallel kernels: they take the same arguments and write the same state for any n_commit.
+  if (dk == 128 && T >= (kda ? kChunkedFromKda : kChunkedFromGdn)) {
     if (launch) launch->chunked = true;
     return sa::chunked_steps(kda, true, name, q, k, v, alpha, beta, state_in, state_out, out, slot_idx, req_idx, n_req, B, T, H, Hk, dk,
                              dv, scale, n_commit, n_commit_rows, nullptr);

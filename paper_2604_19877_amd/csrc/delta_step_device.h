@@ -53,16 +53,18 @@ struct StepOperands {
   uint2 v;
 };
 
-template <int DK, int DV, bool KDA>
+template <int DK, int DV, bool KDA, bool WITH_KQ = true>
 __device__ __forceinline__ void load_operands(StepOperands<DK / 8>& o, const DeltaParams& p, size_t bt, int h, int hk, int row0,
                                               int col0, int turn) {
   constexpr int RPL = DK / 8;
-  const uint2* kp = reinterpret_cast<const uint2*>(p.k + (bt * p.Hk + hk) * DK + row0);
-  const uint2* qp = reinterpret_cast<const uint2*>(p.q + (bt * p.Hk + hk) * DK + row0);
+  if constexpr (WITH_KQ) {
+    const uint2* kp = reinterpret_cast<const uint2*>(p.k + (bt * p.Hk + hk) * DK + row0);
+    const uint2* qp = reinterpret_cast<const uint2*>(p.q + (bt * p.Hk + hk) * DK + row0);
 #pragma unroll
-  for (int j = 0; j < RPL / 4; ++j) {
-    o.k[j] = kp[(j + turn) & (RPL / 4 - 1)];
-    o.q[j] = qp[(j + turn) & (RPL / 4 - 1)];
+    for (int j = 0; j < RPL / 4; ++j) {
+      o.k[j] = kp[(j + turn) & (RPL / 4 - 1)];
+      o.q[j] = qp[(j + turn) & (RPL / 4 - 1)];
+    }
   }
   o.v = *reinterpret_cast<const uint2*>(p.v + (bt * p.H + h) * DV + col0);
   o.beta = load_uniform(p.beta, bt * p.H + h);
@@ -125,16 +127,36 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   // would put a full memory latency on the critical path of every tile.
   StepOperands<RPL> cur, nxt;
   float4 gate_vec[RPL / 4];  // KDA, one token per call: this lane's gates straight from memory
-  load_operands<DK, DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0, turn);
-  // KDA over several tokens: every wavefront fetches the gate vectors of all its steps once, coalesced (DK floats per
-  // step), and parks them in a region of LDS of its own; a step then reads its lane's rows from there.  Per-lane
-  // global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row), as many load
-  // instructions per 4 steps as the state tile itself takes.  No other wavefront reads the region: no barrier.
-  constexpr int kGateSteps = DK == 128 ? 4 : 16;  // longer calls at 128x128 run on the chunk-parallel kernels
+  load_operands<DK, DV, KDA, !MULTI>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0, turn);
+  // Several tokens per call: every wavefront fetches k and q (and KDA's gate vectors) of all its steps once, coalesced
+  // (DK values each per step), and parks them in a region of LDS of its own; a step then reads its lane's rows from
+  // there.  Per-lane global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row): as
+  // many load instructions per 4 steps as the state tile itself takes, and a second set of operand registers to hide
+  // their latency.  No other wavefront reads the region: no barrier.
+  constexpr int kGateSteps = DK == 128 ? 6 : 16;  // longer calls at 128x128 run on the chunk-parallel kernels
   constexpr bool kGatesInLds = KDA && MULTI;
   __shared__ float gate_lds[kGatesInLds ? (DV / 32) * kGateSteps * DK : 1];
+  __shared__ uint32_t kq_lds[MULTI ? (DV / 32) * kGateSteps * DK : 1];  // per (wavefront, step): DK/2 words of k, DK/2 of q
   float* const my_gates = gate_lds + (kGatesInLds ? wave * kGateSteps * DK : 0);
+  uint32_t* const my_kq = kq_lds + (MULTI ? wave * kGateSteps * DK : 0);
   float2 gate_fetch[kGatesInLds ? kGateSteps : 1];
+  uint32_t k_fetch[MULTI ? kGateSteps : 1], q_fetch[MULTI ? kGateSteps : 1];
+  if constexpr (MULTI) {
+    const uint32_t* const ksrc = reinterpret_cast<const uint32_t*>(p.k + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
+    const uint32_t* const qsrc = reinterpret_cast<const uint32_t*>(p.q + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
+    const size_t step_words = static_cast<size_t>(p.Hk) * DK / 2;
+#pragma unroll
+    for (int t = 0; t < kGateSteps; ++t) {
+      if (t < T) {
+        if constexpr (DK == 128) {
+          k_fetch[t] = ksrc[t * step_words + lane];
+          q_fetch[t] = qsrc[t * step_words + lane];
+        } else {  // 32 words each: the lower half of the wavefront fetches k, the upper half q
+          k_fetch[t] = (lane < 32 ? ksrc : qsrc)[t * step_words + (lane & 31)];
+        }
+      }
+    }
+  }
   if constexpr (kGatesInLds) {
     const float* const src = p.alpha + (static_cast<size_t>(b) * T * p.H + h) * DK;
 #pragma unroll
@@ -153,14 +175,22 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
 #pragma unroll
   for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + 4 * turn) & (RPL - 1)) * DV);
   __builtin_amdgcn_sched_barrier(0);
-  if constexpr (kGatesInLds) {
+  if constexpr (MULTI) {
 #pragma unroll
     for (int t = 0; t < kGateSteps; ++t) {
       if (t < T) {
-        if constexpr (DK == 128)
-          *reinterpret_cast<float2*>(my_gates + t * DK + 2 * lane) = gate_fetch[t];
-        else
-          my_gates[t * DK + lane] = gate_fetch[t].x;
+        if constexpr (DK == 128) {
+          my_kq[t * DK + lane] = k_fetch[t];
+          my_kq[t * DK + DK / 2 + lane] = q_fetch[t];
+        } else {
+          my_kq[t * DK + lane] = k_fetch[t];  // lanes 32..63 hold q words, which sit right behind the k words
+        }
+        if constexpr (kGatesInLds) {
+          if constexpr (DK == 128)
+            *reinterpret_cast<float2*>(my_gates + t * DK + 2 * lane) = gate_fetch[t];
+          else
+            my_gates[t * DK + lane] = gate_fetch[t].x;
+        }
       }
     }
     wave_lds_sync();
@@ -174,8 +204,14 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   for (int t = 0; t < T; ++t) {
     const size_t bt = static_cast<size_t>(b) * T + t;
     if constexpr (MULTI) {
-      if (t + 1 < T) load_operands<DK, DV, KDA>(nxt, p, bt + 1, h, hk, row0, col0, turn);
+      if (t + 1 < T) load_operands<DK, DV, KDA, false>(nxt, p, bt + 1, h, hk, row0, col0, turn);
       __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < RPL / 4; ++j) {
+        const int word = (row0 + 4 * ((j + turn) & (RPL / 4 - 1))) / 2;
+        cur.k[j] = *reinterpret_cast<const uint2*>(my_kq + t * DK + word);
+        cur.q[j] = *reinterpret_cast<const uint2*>(my_kq + t * DK + DK / 2 + word);
+      }
     }
     float kf[RPL], qf[RPL];
     unpack_bf16<RPL>(cur.k, kf);

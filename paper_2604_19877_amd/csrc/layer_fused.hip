@@ -125,7 +125,7 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
   if (total == 0) return SA_OK;
   const auto needs_multi = [](const sa::DeltaLaunch& l) { return l.rows && (l.p.T != 1 || l.p.n_commit != 1 || l.p.n_commit_rows); };
   const bool multi = needs_multi(kda) || needs_multi(gdn);
-  SA_REQUIRE(!kda.chunked && !gdn.chunked, SA_EUNSUPPORTED, "%s: calls of 5 and more tokens run on kernels of their own", name);
+  SA_REQUIRE(!kda.chunked && !gdn.chunked, SA_EUNSUPPORTED, "%s: calls this long run on the chunk-parallel kernels, which are launched on their own", name);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (n_fa + n_swa == 0) {
     RecurrentLayerParams rp = {};
