@@ -127,21 +127,21 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   // would put a full memory latency on the critical path of every tile.
   StepOperands<RPL> cur, nxt;
   float4 gate_vec[RPL / 4];  // KDA, one token per call: this lane's gates straight from memory
-  load_operands<DK, DV, KDA, !MULTI>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0, turn);
+  load_operands<DK, DV, KDA, false>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0, turn);
   // Several tokens per call: every wavefront fetches k and q (and KDA's gate vectors) of all its steps once, coalesced
   // (DK values each per step), and parks them in a region of LDS of its own; a step then reads its lane's rows from
   // there.  Per-lane global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row): as
   // many load instructions per 4 steps as the state tile itself takes, and a second set of operand registers to hide
   // their latency.  No other wavefront reads the region: no barrier.
-  constexpr int kGateSteps = DK == 128 ? 6 : 16;  // longer calls at 128x128 run on the chunk-parallel kernels
-  constexpr bool kGatesInLds = KDA && MULTI;
+  constexpr int kGateSteps = !MULTI ? 1 : DK == 128 ? 6 : 16;  // longer calls at 128x128 run on the chunk-parallel kernels
+  constexpr bool kGatesInLds = KDA;
   __shared__ float gate_lds[kGatesInLds ? (DV / 32) * kGateSteps * DK : 1];
-  __shared__ uint32_t kq_lds[MULTI ? (DV / 32) * kGateSteps * DK : 1];  // per (wavefront, step): DK/2 words of k, DK/2 of q
+  __shared__ uint32_t kq_lds[(DV / 32) * kGateSteps * DK];  // per (wavefront, step): DK/2 words of k, DK/2 of q
   float* const my_gates = gate_lds + (kGatesInLds ? wave * kGateSteps * DK : 0);
-  uint32_t* const my_kq = kq_lds + (MULTI ? wave * kGateSteps * DK : 0);
+  uint32_t* const my_kq = kq_lds + wave * kGateSteps * DK;
   float2 gate_fetch[kGatesInLds ? kGateSteps : 1];
-  uint32_t k_fetch[MULTI ? kGateSteps : 1], q_fetch[MULTI ? kGateSteps : 1];
-  if constexpr (MULTI) {
+  uint32_t k_fetch[kGateSteps], q_fetch[kGateSteps];
+  {
     const uint32_t* const ksrc = reinterpret_cast<const uint32_t*>(p.k + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
     const uint32_t* const qsrc = reinterpret_cast<const uint32_t*>(p.q + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
     const size_t step_words = static_cast<size_t>(p.Hk) * DK / 2;
@@ -175,7 +175,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
 #pragma unroll
   for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + 4 * turn) & (RPL - 1)) * DV);
   __builtin_amdgcn_sched_barrier(0);
-  if constexpr (MULTI) {
+  {
 #pragma unroll
     for (int t = 0; t < kGateSteps; ++t) {
       if (t < T) {
@@ -206,6 +206,8 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
     if constexpr (MULTI) {
       if (t + 1 < T) load_operands<DK, DV, KDA, false>(nxt, p, bt + 1, h, hk, row0, col0, turn);
       __builtin_amdgcn_sched_barrier(0);
+    }
+    {
 #pragma unroll
       for (int j = 0; j < RPL / 4; ++j) {
         const int word = (row0 + 4 * ((j + turn) & (RPL / 4 - 1))) / 2;

@@ -149,8 +149,10 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
     p.end_fa = static_cast<int>(n_prev + n_fa);
     p.end_swa = static_cast<int>(n_prev + n_fa + n_swa);
     p.end_kda = static_cast<int>(n_prev + n_fa + n_swa + n_kda);
+    // The multi-token tile body parks k, q and gate vectors of up to 6 steps in LDS (24 KiB): with the attention body's
+    // 32.5 KiB that already limits a CU to the 2 workgroups the K/V stream wants, so no padding is requested.
     if (multi)
-      sa::launch(SA_K_LAYER, layer_decode_kernel<true>, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
+      sa::launch(SA_K_LAYER, layer_decode_kernel<true>, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, p);
     else
       sa::launch(SA_K_LAYER, layer_decode_kernel<false>, dim3(static_cast<unsigned>(total)), dim3(256), kOccupancyPadBytes, s, p);
   }
