@@ -31,7 +31,7 @@ N_STATE_SETS = 8      # 8 x 128 MiB per recurrent mixer: the working set exceeds
 N_RING = 8            # distinct pre-staged operand sets
 # HBM bytes per launch of the full-attention split kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by the copy-kernel calibration (profiles/batch64_step_all_kernels_hbm_bytes.txt).
-FA_SPLIT_TRAFFIC_BYTES = 8599021568
+FA_SPLIT_TRAFFIC_BYTES = 8599005184
 
 
 def parse_args():
