@@ -10,9 +10,11 @@
 //
 // Work split.  Value columns are independent of each other (every formula above acts column by
 // column), so a wavefront owns 32 columns and all dk rows and never talks to another wavefront:
-// no LDS, no barrier.  Lane (r8 = lane/8, c8 = lane%8) holds columns 4*c8..4*c8+3 of rows
+// no barrier.  Lane (r8 = lane/8, c8 = lane%8) holds columns 4*c8..4*c8+3 of rows
 // r8*dk/8 .. (r8+1)*dk/8-1, i.e. dk/8 float4 registers.  One load instruction of the wavefront
 // fetches 8 full 128-byte lines.  The key-dimension sums finish with a 3-step butterfly over r8.
+// k, q and KDA's gate vector are fetched once per wavefront, coalesced, and handed to the lanes
+// through a few KiB of LDS that only this wavefront touches.
 #include "common.h"
 #include "delta_step_device.h"
 
