@@ -29,6 +29,8 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
 // 53.2 us on the register-resident kernel against 54.2 us chunked, 6 tokens 54.2 against 53.4; KDA 5 tokens 53.6 against
 // 59.7 us, 6 tokens 56.1 against 59.0, 8 tokens 62.6 against 59.8).  The register-resident kernel holds room for 6 steps.
 constexpr int kChunkedFromGdn = 5, kChunkedFromKda = 7;
+static_assert(kChunkedFromGdn - 1 <= kMaxRegisterSteps128 && kChunkedFromKda - 1 <= kMaxRegisterSteps128,
+              "the register-resident kernel must have room for every call that is not chunked");
 
 }  // namespace
 
@@ -42,6 +44,7 @@ sa_status sa::delta_prepare(bool kda, const void* q, const void* k, const void* 
     launch->rows = 0;
     launch->chunked = false;
   }
+  static_assert(kMaxRegisterSteps64 == 16, "the entry points admit up to 16 tokens per call");
   SA_REQUIRE(B >= 0 && T >= 1 && T <= 16, SA_EINVAL, "%s: need B >= 0 and 1 <= T <= 16 (B=%d, T=%d)", name, B, T);
   SA_REQUIRE(H >= 1 && Hk >= 1 && H % Hk == 0, SA_EINVAL, "%s: H must be a positive multiple of Hk (H=%d, Hk=%d)", name, H, Hk);
   SA_REQUIRE(n_commit >= 0 && n_commit <= T, SA_EINVAL, "%s: n_commit=%d outside [0,T=%d]", name, n_commit, T);

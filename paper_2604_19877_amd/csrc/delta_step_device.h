@@ -45,6 +45,10 @@ namespace {
 
 using sa::DeltaParams;
 
+// Steps per call for which the multi-token tile body has LDS room at 128x128 (longer calls run on the chunk-parallel
+// kernels) and at 64x64 (the entry points' limit).
+constexpr int kMaxRegisterSteps128 = 6, kMaxRegisterSteps64 = 16;
+
 // Operands of one step as they arrive from memory (bf16 still packed).
 template <int RPL>
 struct StepOperands {
@@ -133,7 +137,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   // there.  Per-lane global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row): as
   // many load instructions per 4 steps as the state tile itself takes, and a second set of operand registers to hide
   // their latency.  No other wavefront reads the region: no barrier.
-  constexpr int kGateSteps = !MULTI ? 1 : DK == 128 ? 6 : 16;  // longer calls at 128x128 run on the chunk-parallel kernels
+  constexpr int kGateSteps = !MULTI ? 1 : DK == 128 ? kMaxRegisterSteps128 : kMaxRegisterSteps64;
   constexpr bool kGatesInLds = KDA;
   __shared__ float gate_lds[kGatesInLds ? (DV / 32) * kGateSteps * DK : 1];
   __shared__ uint32_t kq_lds[(DV / 32) * kGateSteps * DK];  // per (wavefront, step): DK/2 words of k, DK/2 of q
