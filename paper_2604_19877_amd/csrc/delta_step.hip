@@ -28,7 +28,7 @@ __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
 // Tokens per call from which the decode steps run on the chunk-parallel kernels (measured at batch 64: GDN 5 tokens
 // 53.2 us on the register-resident kernel against 54.2 us chunked, 6 tokens 54.2 against 53.4; KDA 5 tokens 53.6 against
 // 59.7 us, 6 tokens 56.1 against 59.0, 8 tokens 62.6 against 59.8).  The register-resident kernel holds room for 6 steps.
-constexpr int kChunkedFromGdn = 5, kChunkedFromKda = 7;
+constexpr int kChunkedFromGdn = 6, kChunkedFromKda = 7;
 static_assert(kChunkedFromGdn - 1 <= kMaxRegisterSteps128 && kChunkedFromKda - 1 <= kMaxRegisterSteps128,
               "the register-resident kernel must have room for every call that is not chunked");
 
