@@ -123,7 +123,7 @@ sa_status kda_chunk_steps(const void* q, const void* k, const void* v, const flo
  * post-processing fused around it in one launch (Appendix B: a short causal 1-D convolution with SiLU on
  * Q, K and V, L2-normalised q and k, beta = sigmoid(beta_raw), log-decay
  * g = -exp(A_log) * softplus(alpha_raw + dt_bias), gated RMS normalisation of the read-out with z; Section 6:
- * decode "updates the state in-place with incremental convolution updates").  One new token per row.
+ * the decode step updates the recurrent state and the convolution histories in place).  One new token per row.
  *
  * Per processed row b (slot s = slot_idx ? slot_idx[b] : b), with C the channel count of a stream
  * (Hk*dk for q and k, H*dv for v) and Kc = conv_taps:
@@ -285,9 +285,12 @@ sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_
  * One unified page is the recurrent state of one (sequence, layer): H*dk*dv*4 bytes.  For an attention
  * layer the same page holds the K and V blocks of sa_pool_tokens_per_page() tokens: first the K blocks of
  * its 16-token pages, then, from the middle of the page, their V blocks.  With
- *     kpool = arena,  vpool = arena + page_bytes/2,  n_pages(kernel) = n_pages * sa_pool_kv_id_stride()
+ *     kpool = arena,  vpool = arena + page_bytes/2,  n_pages(kernel) = sa_pool_kernel_pages()
  * the 16-token page i of unified page u has the kernel page id u * sa_pool_kv_id_stride() + i, and the
- * attention and append entry points above work on the arena unchanged.  For a recurrent layer
+ * attention and append entry points above work on the arena unchanged.  sa_pool_kernel_pages() is
+ * n_pages * sa_pool_kv_id_stride() - sa_pool_kv_id_stride()/2, one past the last id whose K and V blocks both
+ * lie inside the arena (the V block of an id sits half a unified page behind its K block), so that the kernels'
+ * clamp of a bad table entry stays inside the arena for V as well.  For a recurrent layer
  *     state = (float*)arena,  slot = u
  * (convolution histories, if used, live in caller arrays indexed by the same slot).
  * Requires page_bytes to be a multiple of 2 * Hkv*16*D*2 (SA_EUNSUPPORTED otherwise).
@@ -303,6 +306,7 @@ void sa_pool_destroy(sa_pool* pool);
 size_t sa_pool_page_bytes(const sa_pool* pool);
 int sa_pool_tokens_per_page(const sa_pool* pool);
 int sa_pool_kv_id_stride(const sa_pool* pool);
+int sa_pool_kernel_pages(const sa_pool* pool);
 int sa_pool_free_pages(const sa_pool* pool);
 sa_status sa_pool_seq_create(sa_pool* pool, const char* placement, int* seq_id_out);
 sa_status sa_pool_seq_reserve(sa_pool* pool, int seq_id, int len, int window, int slack);

@@ -76,6 +76,7 @@ _SIGNATURES = {
     "sa_pool_page_bytes": (c_size_t, [c_void_p]),
     "sa_pool_tokens_per_page": (c_int, [c_void_p]),
     "sa_pool_kv_id_stride": (c_int, [c_void_p]),
+    "sa_pool_kernel_pages": (c_int, [c_void_p]),
     "sa_pool_free_pages": (c_int, [c_void_p]),
     "sa_pool_seq_create": (c_int, [c_void_p, c_char_p, ctypes.POINTER(c_int)]),
     "sa_pool_seq_reserve": (c_int, [c_void_p, c_int, c_int, c_int, c_int]),
@@ -290,6 +291,10 @@ def sa_pool_tokens_per_page(pool) -> int:
 
 def sa_pool_kv_id_stride(pool) -> int:
     return lib().sa_pool_kv_id_stride(pool)
+
+
+def sa_pool_kernel_pages(pool) -> int:
+    return lib().sa_pool_kernel_pages(pool)
 
 
 def sa_pool_free_pages(pool) -> int:

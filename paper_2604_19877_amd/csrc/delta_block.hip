@@ -1,9 +1,9 @@
 // Whole-block decode step of GDN / KDA: causal conv + SiLU, L2 norm, gate activations, the
 // delta-rule state update and the gated RMS norm of the read-out in one launch, gfx950.
 //
-// Appendix B of the paper lists these operations around the recurrence and Section 6 says decode
-// updates the state in place "with incremental convolution updates"; separately they are four tiny
-// launches around a 48 us one.  Here the workgroup that owns a 128x128 state tile first requests the
+// Appendix B of the paper lists these operations around the recurrence and Section 6 has the decode
+// step update the recurrent state and the convolution histories in place; separately they are four
+// tiny launches around a 48 us one.  Here the workgroup that owns a 128x128 state tile first requests the
 // tile (16 non-temporal loads per lane, in flight during everything that follows), then its 256
 // threads compute the 128 q, 128 k and 128 v channels of this head, one channel per thread:
 // Kc-tap depthwise convolution over the stored inputs and the new one, SiLU, and the shifted

@@ -67,6 +67,11 @@ extern "C" void sa_pool_destroy(sa_pool* pool) { delete pool; }
 extern "C" size_t sa_pool_page_bytes(const sa_pool* pool) { return pool ? pool->page_bytes : 0; }
 extern "C" int sa_pool_tokens_per_page(const sa_pool* pool) { return pool ? pool->tokens_per_page : 0; }
 extern "C" int sa_pool_kv_id_stride(const sa_pool* pool) { return pool ? 2 * pool->kv_pages_per_page : 0; }
+// One past the largest 16-token page id whose K block and V block both lie inside the arena: the ids of the last unified
+// page stop at its middle, because the V block of id i sits half a unified page behind its K block.
+extern "C" int sa_pool_kernel_pages(const sa_pool* pool) {
+  return pool ? (2 * pool->n_pages - 1) * pool->kv_pages_per_page : 0;
+}
 extern "C" int sa_pool_free_pages(const sa_pool* pool) { return pool ? static_cast<int>(pool->free_list.size()) : 0; }
 
 extern "C" sa_status sa_pool_seq_create(sa_pool* pool, const char* placement, int* seq_id_out) {
@@ -130,20 +135,26 @@ extern "C" sa_status sa_pool_seq_reserve(sa_pool* pool, int seq_id, int len, int
   }
   SA_REQUIRE(need <= static_cast<long long>(pool->free_list.size()) + give, SA_ENOMEM,
              "%s: %lld pages needed, %zu free (+%lld released by the window)", name, need, pool->free_list.size(), give);
+  // Second pass, in two sweeps over the layers: first every sliding-window layer returns the pages behind its window,
+  // then pages are taken.  The count above is over the whole sequence, so a layer may only take once every layer has
+  // given (taking layer by layer could empty the free list before a later layer's release refills it).
+  for (int l = 0; l < pool->n_layers; ++l) {
+    if (s->placement[l] != 'S') continue;
+    std::vector<int32_t>& pg = s->pages[l];
+    for (int j = 0; j < first_s && j < static_cast<int>(pg.size()); ++j)
+      if (pg[j] >= 0) {
+        pool->free_list.push_back(pg[j]);
+        pg[j] = -1;
+      }
+  }
   for (int l = 0; l < pool->n_layers; ++l) {
     const char c = s->placement[l];
     if (!is_attention(c)) continue;
     std::vector<int32_t>& pg = s->pages[l];
     if (static_cast<int>(pg.size()) < n_blocks) pg.resize(n_blocks, -1);
-    const int first = c == 'S' ? first_s : 0;
-    for (int j = 0; j < first && j < static_cast<int>(pg.size()); ++j)
-      if (pg[j] >= 0) {
-        pool->free_list.push_back(pg[j]);
-        pg[j] = -1;
-      }
-    for (int j = first; j < n_blocks; ++j)
+    for (int j = c == 'S' ? first_s : 0; j < n_blocks; ++j)
       if (pg[j] < 0) {
-        pg[j] = pool->free_list.back();
+        pg[j] = pool->free_list.back();   // cannot be empty: need <= free + give was checked above
         pool->free_list.pop_back();
       }
   }

@@ -51,7 +51,7 @@ def test_decode_loop_on_a_pooled_arena():
         for b in range(B):
             n = int(lens[b])
             sa.kv_append(dev(hist[l]["k_tok"][b:b + 1, :n]), dev(hist[l]["v_tok"][b:b + 1, :n]), kpool_ptr, vpool_ptr,
-                         n_unified * stride, dev(table[b:b + 1]), max_pages, dev(np.zeros(1, dtype=np.int32)), 1, n, HKV, D, 16)
+                         sa.sa_pool_kernel_pages(pool), dev(table[b:b + 1]), max_pages, dev(np.zeros(1, dtype=np.int32)), 1, n, HKV, D, 16)
     torch.cuda.synchronize()
     free_after_prefill = sa.sa_pool_free_pages(pool)
     # FSKG@600: F 2 + S 2(blocks 0..1 both touch [344,600)) + 2 states; GKSF@1100: 2 + S 2 + F 3; SFFK@50: 1+1+1+1
@@ -69,7 +69,7 @@ def test_decode_loop_on_a_pooled_arena():
             t_table, t_slot, t_len = dev(table), dev(np.maximum(slot, 0)), dev(cur + 1)
             k_new = np.stack([hist[l]["k_tok"][b, cur[b]] for b in range(B)])[:, None]
             v_new = np.stack([hist[l]["v_tok"][b, cur[b]] for b in range(B)])[:, None]
-            sa.kv_append(dev(k_new), dev(v_new), kpool_ptr, vpool_ptr, n_unified * stride, t_table, max_pages, dev(cur), B, 1,
+            sa.kv_append(dev(k_new), dev(v_new), kpool_ptr, vpool_ptr, sa.sa_pool_kernel_pages(pool), t_table, max_pages, dev(cur), B, 1,
                          HKV, D, 16)
             r = gen.recurrent_inputs(9100 + 10 * step + l, B, 1, H, H, DK, DV, False)
             rv = gen.recurrent_inputs(9200 + 10 * step + l, B, 1, H, H, DK, DV, True)
@@ -82,7 +82,7 @@ def test_decode_loop_on_a_pooled_arena():
             rec_ops.append((r, rv, qa, slot))
             ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["a_s"], alpha_vec=t["a_v"], beta=t["beta"],
                                         state=arena.data_ptr(), slot_idx=t_slot, q_attn=t["qa"], kpool=kpool_ptr, vpool=vpool_ptr,
-                                        n_pages=n_unified * stride, page_table=t_table, seq_lens=t_len, max_pages=max_pages,
+                                        n_pages=sa.sa_pool_kernel_pages(pool), page_table=t_table, seq_lens=t_len, max_pages=max_pages,
                                         max_seq_len=max_pages * 16, out=t["out"]))
         sa.placement_decode(plan, ios, shapes, 1, window, D ** -0.5, DK ** -0.5, ws, ws_bytes)
         torch.cuda.synchronize()

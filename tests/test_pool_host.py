@@ -32,6 +32,11 @@ def test_geometry_follows_the_15b_shapes(pool):
     assert sa.sa_pool_page_bytes(pool) == 32 * 128 * 128 * 4 == 2 << 20
     assert sa.sa_pool_tokens_per_page(pool) == 512
     assert sa.sa_pool_kv_id_stride(pool) == 64
+    # the kernels' page bound: the last id whose V block (half a unified page behind its K block) is still in the arena, + 1
+    assert sa.sa_pool_kernel_pages(pool) == 40 * 64 - 32
+    last = sa.sa_pool_kernel_pages(pool) - 1
+    block = 8 * 16 * 128 * 2
+    assert (2 << 20) // 2 + (last + 1) * block == 40 * (2 << 20)
     assert sa.sa_pool_free_pages(pool) == 40
 
 
@@ -114,6 +119,77 @@ def test_a_sliding_window_sequence_runs_forever_in_bounded_space(pool):
     n = 59881
     live = np.flatnonzero(table[0] >= 0)
     assert live.min() * 16 <= n - 4096 - 3 and live.max() * 16 + 16 >= n
+
+
+def test_a_length_jump_past_the_window_on_a_nearly_full_pool():
+    # An F layer ahead of an S layer, 7 pages, window 1024: the second reserve needs 3 more pages for F while only 2 are
+    # free; the third comes from the S layer, whose first two blocks fall behind the window.  Every S layer has to give
+    # before any layer takes, or the F layer empties the free list and pages end up mapped twice.
+    p = sa.sa_pool_create(7, SHAPES, 2)
+    try:
+        s = sa.sa_pool_seq_create(p, "FS")
+        sa.sa_pool_seq_reserve(p, s, 1535, 1024)                   # blocks 0..2 on both layers: 6 pages, 1 free
+        assert (sa.sa_pool_free_pages(p), sa.sa_pool_seq_pages(p, s)) == (1, 6)
+        sa.sa_pool_seq_reserve(p, s, 2560, 1024)                   # F: blocks 0..4; S: tokens [1536, 2560) = blocks 3..4
+        assert (sa.sa_pool_free_pages(p), sa.sa_pool_seq_pages(p, s)) == (0, 7)
+        stride = sa.sa_pool_kv_id_stride(p)
+        used = []
+        for layer in range(2):
+            table, _ = sa.sa_pool_layer_tables(p, [s], layer, 5 * 32)
+            used += sorted({int(e) // stride for e in table[0] if e >= 0})
+        assert sorted(used) == list(range(7))                      # every page exactly once
+        table_s, _ = sa.sa_pool_layer_tables(p, [s], 1, 5 * 32)
+        assert (table_s[0, :3 * 32] == -1).all() and (table_s[0, 3 * 32:] >= 0).all()
+        # one page too many: refused, nothing changes
+        with pytest.raises(sa.SaError) as e:
+            sa.sa_pool_seq_reserve(p, s, 3073, 1024)
+        assert e.value.status == sa.SA_ENOMEM
+        assert (sa.sa_pool_free_pages(p), sa.sa_pool_seq_pages(p, s)) == (0, 7)
+        sa.sa_pool_seq_free(p, s)
+        assert sa.sa_pool_free_pages(p) == 7
+    finally:
+        sa.sa_pool_destroy(p)
+
+
+def test_random_reserves_keep_the_books_balanced():
+    rng = np.random.default_rng(77)
+    for trial in range(20):
+        n_pages, L = int(rng.integers(6, 30)), int(rng.integers(1, 5))
+        p = sa.sa_pool_create(n_pages, SHAPES, L)
+        try:
+            seqs = {}
+            for _ in range(60):
+                if seqs and rng.random() < 0.15:
+                    s = list(seqs)[int(rng.integers(len(seqs)))]
+                    sa.sa_pool_seq_free(p, s)
+                    del seqs[s]
+                elif len(seqs) < 3 and rng.random() < 0.3:
+                    try:
+                        seqs[sa.sa_pool_seq_create(p, "".join(rng.choice(list("FSKG"), L)))] = 0
+                    except sa.SaError as e:
+                        assert e.status == sa.SA_ENOMEM
+                elif seqs:
+                    s = list(seqs)[int(rng.integers(len(seqs)))]
+                    n = seqs[s] + int(rng.integers(1, 3000))
+                    before = (sa.sa_pool_free_pages(p), sa.sa_pool_seq_pages(p, s))
+                    try:
+                        sa.sa_pool_seq_reserve(p, s, n, int(rng.integers(1, 2000)), int(rng.integers(0, 4)))
+                        seqs[s] = n
+                    except sa.SaError as e:
+                        assert e.status == sa.SA_ENOMEM
+                        assert (sa.sa_pool_free_pages(p), sa.sa_pool_seq_pages(p, s)) == before
+                held = sum(sa.sa_pool_seq_pages(p, s) for s in seqs)
+                assert held + sa.sa_pool_free_pages(p) == n_pages
+                stride = sa.sa_pool_kv_id_stride(p)
+                used = []
+                for layer in range(L):
+                    table, slot = sa.sa_pool_layer_tables(p, list(seqs), layer, max(seqs.values(), default=0) // 16 + 32)
+                    used += [int(x) for x in slot if x >= 0]
+                    for row in table:
+                        used += sorted({int(e) // stride for e in row if e >= 0})
+                assert len(used) == len(set(used)) == held
+        finally:
+            sa.sa_pool_destroy(p)
 
 
 def test_argument_errors(pool):
