@@ -210,6 +210,21 @@ sa_status attn_decode(const void* q, const void* kpool, const void* vpool, int n
                       int B, int T, int Hq, int Hkv, int D, int page_size, int max_seq_len, int window, float scale,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* attn_decode for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and results (bit for bit) as
+ * attn_decode, without the workspace: the per-range partial results live in a fixed device array of
+ * attn_decode_static_max_bytes() = 16 MiB that is part of the library's image (every GPU the library runs on holds
+ * its copy until the process ends).  The call allocates and frees nothing.  SA_EWORKSPACE, with nothing enqueued, if
+ * attn_decode_workspace_bytes() of the call exceeds that size (batch 64 at 32768 tokens needs 8.1 MiB).
+ * All calls on one GPU share the array: it keeps the last call's partial results (every value a call reads it has
+ * written itself first, so nothing needs clearing), and two calls that overlap in time on one GPU (different
+ * streams) race; calls on one stream are ordered and safe. */
+size_t attn_decode_static_max_bytes(void);
+sa_status attn_decode_static(const void* q, const void* kpool, const void* vpool, int n_pages,
+                             const int32_t* page_table, int max_pages, const int32_t* seq_lens, const int32_t* req_idx, int n_req,
+                             float* out, int B, int T, int Hq, int Hkv, int D, int page_size, int max_seq_len, int window,
+                             float scale, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Placement decode (Section 6, "Per-request placement switching": each request names a placement,
  * a placement names one mixer per layer, and the layer dispatches on it with no global state).

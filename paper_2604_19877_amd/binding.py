@@ -64,6 +64,9 @@ _SIGNATURES = {
     "attn_decode_workspace_bytes": (c_size_t, [c_int] * 7),
     "attn_decode": (c_int, [c_void_p] * 3 + [c_int, c_void_p, c_int, c_void_p, c_void_p, c_int, c_void_p] + [c_int] * 8
                     + [c_float, c_void_p, c_size_t, c_void_p]),
+    "attn_decode_static_max_bytes": (c_size_t, []),
+    "attn_decode_static": (c_int, [c_void_p] * 3 + [c_int, c_void_p, c_int, c_void_p, c_void_p, c_int, c_void_p] + [c_int] * 8
+                           + [c_float, c_void_p]),
     "placement_plan_create": (c_int, [ctypes.POINTER(c_char_p), c_int, c_int, ctypes.POINTER(c_int32), c_int,
                                       ctypes.POINTER(c_void_p)]),
     "placement_plan_destroy": (None, [c_void_p]),
@@ -226,6 +229,17 @@ def attn_decode(q, kpool, vpool, n_pages, page_table, max_pages, seq_lens, req_i
     _check(lib().attn_decode(_ptr(q), _ptr(kpool), _ptr(vpool), n_pages, _ptr(page_table), max_pages, _ptr(seq_lens),
                              _ptr(req_idx), n_req, _ptr(out), B, T, Hq, Hkv, D, page_size, max_seq_len, window, scale,
                              _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def attn_decode_static_max_bytes() -> int:
+    return lib().attn_decode_static_max_bytes()
+
+
+def attn_decode_static(q, kpool, vpool, n_pages, page_table, max_pages, seq_lens, req_idx, n_req, out, B, T, Hq, Hkv, D,
+                       page_size, max_seq_len, window, scale, stream=None):
+    _check(lib().attn_decode_static(_ptr(q), _ptr(kpool), _ptr(vpool), n_pages, _ptr(page_table), max_pages, _ptr(seq_lens),
+                                    _ptr(req_idx), n_req, _ptr(out), B, T, Hq, Hkv, D, page_size, max_seq_len, window, scale,
+                                    _stream(stream)))
 
 
 def placement_plan_create(placements, placement_id):

@@ -21,6 +21,8 @@
 // keeps that same row in the lane, so the whole online softmax is lane-local except for a 2-step
 // maximum over the 4 token groups.  Probabilities are split into two bf16 terms (p = hi + lo) so the
 // second product carries ~16 mantissa bits of p instead of 8; its 32-wide contraction runs over (token, term).
+#include <mutex>
+
 #include "attn_device.h"
 #include "common.h"
 
@@ -229,6 +231,62 @@ extern "C" sa_status attn_decode(const void* q, const void* kpool, const void* v
                                  size_t workspace_bytes, void* stream) {
   return attn_decode_impl(false, q, kpool, vpool, n_pages, page_table, max_pages, seq_lens, req_idx, n_req, out, B, T, Hq, Hkv, D,
                           page_size, max_seq_len, window, scale, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// attn_decode for callers that cannot allocate: the partial results of the page ranges live in a device array that
+// is part of the library's image instead of a caller workspace.
+constexpr size_t kScratchBytes = size_t{16} << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// The address of `scratch` on the current device (every device holds its own copy at its own address), looked up
+// once per device.  In host code the array's name is only a handle for this lookup, never a device address.
+sa_status scratch_address(void** ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return sa::fail(SA_EHIP, "attn_decode_static: hipGetDevice: %s", hipGetErrorString(e));
+  SA_REQUIRE(dev >= 0 && dev < kMaxDevices, SA_EUNSUPPORTED, "attn_decode_static: device index %d beyond %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return sa::fail(SA_EHIP, "attn_decode_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *ptr_out = g_scratch_ptr[dev];
+  return SA_OK;
+}
+
+}  // namespace
+
+extern "C" size_t attn_decode_static_max_bytes(void) { return kScratchBytes; }
+
+extern "C" sa_status attn_decode_static(const void* q, const void* kpool, const void* vpool, int n_pages,
+                                        const int32_t* page_table, int max_pages, const int32_t* seq_lens,
+                                        const int32_t* req_idx, int n_req, float* out, int B, int T, int Hq, int Hkv, int D,
+                                        int page_size, int max_seq_len, int window, float scale, void* stream) {
+  void* ptr = nullptr;
+  sa_status st = scratch_address(&ptr);
+  if (st != SA_OK) return st;
+  // Everything attn_decode checks, with the array as a workspace of its fixed size: a call whose partial results do not
+  // fit is refused (SA_EWORKSPACE) before anything is enqueued.
+  st = attn_decode_impl(false, q, kpool, vpool, n_pages, page_table, max_pages, seq_lens, req_idx, n_req, out, B, T, Hq, Hkv, D,
+                        page_size, max_seq_len, window, scale, ptr, kScratchBytes, stream);
+  if (st == SA_EWORKSPACE)
+    return sa::fail(SA_EWORKSPACE,
+                    "attn_decode_static: the partial results of this call exceed the library's %zu-byte array; use attn_decode with a "
+                    "workspace of attn_decode_workspace_bytes()",
+                    kScratchBytes);
+  return st;
 }
 
 // Argument check of an attention launch without enqueueing anything.
