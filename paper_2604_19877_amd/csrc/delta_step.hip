@@ -22,7 +22,8 @@ namespace {
 
 template <int DK, int DV, bool KDA, bool MULTI>
 __global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
-  delta_step_body<DK, DV, KDA, MULTI>(p, interleaved_tile(blockIdx.x, gridDim.x), blockIdx.x);
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<DK, DV, KDA, MULTI>()];
+  delta_step_body<DK, DV, KDA, MULTI>(p, interleaved_tile(blockIdx.x, gridDim.x), blockIdx.x, park);
 }
 
 // Tokens per call from which the decode steps run on the chunk-parallel kernels (measured at batch 64: GDN 5 tokens

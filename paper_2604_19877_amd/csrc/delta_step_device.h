@@ -49,62 +49,63 @@ using sa::DeltaParams;
 // kernels) and at 64x64 (the entry points' limit).
 constexpr int kMaxRegisterSteps128 = 6, kMaxRegisterSteps64 = 16;
 
-// Operands of one step as they arrive from memory (bf16 still packed).
-template <int RPL>
+// The per-step scalars and value columns of a lane as they arrive from memory (bf16 still packed).
 struct StepOperands {
-  uint2 k[RPL / 4], q[RPL / 4];  // chunk j: the 4 rows this lane holds in registers 4j .. 4j+3
-  float alpha, beta;  // alpha: the scalar gate of GDN (KDA's gate vector is fetched apart)
+  float alpha, beta;  // alpha: the scalar gate of GDN (KDA's gate vector goes through LDS)
   uint2 v;
 };
 
-template <int DK, int DV, bool KDA, bool WITH_KQ = true>
-__device__ __forceinline__ void load_operands(StepOperands<DK / 8>& o, const DeltaParams& p, size_t bt, int h, int hk, int row0,
-                                              int col0, int turn) {
-  constexpr int RPL = DK / 8;
-  if constexpr (WITH_KQ) {
-    const uint2* kp = reinterpret_cast<const uint2*>(p.k + (bt * p.Hk + hk) * DK + row0);
-    const uint2* qp = reinterpret_cast<const uint2*>(p.q + (bt * p.Hk + hk) * DK + row0);
-#pragma unroll
-    for (int j = 0; j < RPL / 4; ++j) {
-      o.k[j] = kp[(j + turn) & (RPL / 4 - 1)];
-      o.q[j] = qp[(j + turn) & (RPL / 4 - 1)];
-    }
-  }
+template <int DV, bool KDA>
+__device__ __forceinline__ void load_operands(StepOperands& o, const DeltaParams& p, size_t bt, int h, int col0) {
   o.v = *reinterpret_cast<const uint2*>(p.v + (bt * p.H + h) * DV + col0);
   o.beta = load_uniform(p.beta, bt * p.H + h);
   o.alpha = KDA ? 1.f : load_uniform(p.alpha, bt * p.H + h);
 }
 
-// KDA's gates of this lane's rows for one step.
+// How a wavefront parks one step's key-dimension vector (k, q or KDA's gates; DK fp32 values) in LDS for its lanes.
+// The 8 lane groups r8 each own RPL = DK/8 consecutive rows; group r8's values sit at [r8 * kGroupStride, + RPL) in the
+// order the group's lanes keep their rows in registers: position m holds row (m + rot) mod RPL.  A lane then reads its
+// RPL values as RPL/4 aligned 16-byte loads, whatever `rot` is.  The stride leaves 4 floats between groups so that
+// the 8 groups' 16-byte reads fall into 8 different sets of 4 banks.
 template <int DK>
-__device__ __forceinline__ void load_gate_vector(float4 (&a)[DK / 32], const DeltaParams& p, size_t bt, int h, int row0, int turn) {
-  const float4* ap = reinterpret_cast<const float4*>(p.alpha + (bt * p.H + h) * DK + row0);
-#pragma unroll
-  for (int j = 0; j < DK / 32; ++j) a[j] = ap[(j + turn) & (DK / 32 - 1)];
-}
-
-template <int N>
-__device__ __forceinline__ void unpack_bf16(const uint2 (&src)[N / 4], float (&dst)[N]) {
-#pragma unroll
-  for (int j = 0; j < N / 4; ++j) {
-    dst[4 * j] = bf16_lo(src[j].x);
-    dst[4 * j + 1] = bf16_hi(src[j].x);
-    dst[4 * j + 2] = bf16_lo(src[j].y);
-    dst[4 * j + 3] = bf16_hi(src[j].y);
+struct KeyVecLds {
+  static constexpr int RPL = DK / 8;
+  static constexpr int kGroupStride = RPL + 4;
+  static constexpr int kFloats = 8 * kGroupStride;
+  // where the value of key row `row` goes
+  static __device__ __forceinline__ int slot(int row, int rot) {
+    return (row / RPL) * kGroupStride + ((row - rot) & (RPL - 1));
   }
+};
+
+// Floats of LDS one workgroup of delta_step_body needs: per wavefront and step, the parked k, q (and gate) vectors.
+template <int DK, int DV, bool KDA, bool MULTI>
+constexpr int delta_park_floats() {
+  return (DV / 32) * (!MULTI ? 1 : DK == 128 ? kMaxRegisterSteps128 : kMaxRegisterSteps64) * (KDA ? 3 : 2) * KeyVecLds<DK>::kFloats;
 }
 
 // MULTI = false: exactly one committed step (T == 1, n_commit == 1), the decode hot path, with an
 // unconditional store.  MULTI = true: any T and n_commit with the tile held in registers; the
 // operands of step t+1 are requested before step t is computed.
-// The work of one workgroup (2*DV threads): tile `block` = (row of the request list) * H + head.
-template <int DK, int DV, bool KDA, bool MULTI>
-__device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int block, const int start) {
+// The work of one workgroup (2*DV threads): tile `block` = (row of the request list) * H + head.  park_lds: 16-byte
+// aligned LDS of delta_park_floats<DK, DV, KDA, MULTI>() floats.
+// EITHER (with KDA): one body for both mixers, for kernels whose workgroups run tiles of either kind: a tile with
+// scalar_gate set is a GDN tile, whose one gate is written to all key rows of the parked gate vector; everything after
+// the fetch is the same code, so such a kernel carries one tile body (and its registers) instead of two.
+template <int DK, int DV, bool KDA, bool MULTI, bool EITHER = false>
+__device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int block, const int start, float* const park_lds,
+                                                const bool scalar_gate = false) {
+  static_assert(!EITHER || KDA, "the body for either mixer is the per-channel one");
   constexpr int RPL = DK / 8;  // rows per lane
-  // Register m of a lane holds row (m + 4 * turn) mod RPL of the lane's rows: workgroups launched next to each other
-  // take different turns, so that at any moment they are not all fetching the same 512-byte slice of their tiles
-  // (all tiles are 64 KiB apart, so those slices would all sit on the same few memory channels).
-  const int turn = start & (RPL / 4 - 1);
+  using Park = KeyVecLds<DK>;
+  // Register m of a lane holds row (m + rot) mod RPL of the lane's rows: workgroups launched next to each other start
+  // their walk over the tile at different rows, so that at any moment they are not all fetching (and later storing) the
+  // same 512-byte slice of their tiles (all tiles are 64 KiB apart, so those slices would all sit on the same few memory
+  // channels).  k, q and the gates reach the lanes through LDS already in that rotated order, so any rotation costs the
+  // same; four starting rows a quarter of the lane's rows apart measured best (batch 64 / 256, us per step: no rotation
+  // 47.0 / 183, these four 44.2 / 173.5, all sixteen rows 45.7 / 176, eight 44.9 / 176, the sixteen in bit-swapped
+  // order 44.2 / 176).
+  const int rot = (RPL / 4) * (start & 3);
   const int r = block / p.H;
   const int h = block - r * p.H;
   const int b = p.req_idx ? p.req_idx[r] : r;
@@ -126,31 +127,27 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   const float* sin = p.state_in + tile + static_cast<size_t>(row0) * DV + col0;
   float* sout = p.state_out + tile + static_cast<size_t>(row0) * DV + col0;
 
-  // All requests first: the small operands of step 0, then the 16 state rows of this lane.  The
+  // All requests first: the small operands of step 0, then the RPL state rows of this lane.  The
   // scheduling barrier keeps the compiler from sinking any of them towards its first use, which
   // would put a full memory latency on the critical path of every tile.
-  StepOperands<RPL> cur, nxt;
-  float4 gate_vec[RPL / 4];  // KDA, one token per call: this lane's gates straight from memory
-  load_operands<DK, DV, KDA, false>(cur, p, static_cast<size_t>(b) * T, h, hk, row0, col0, turn);
-  // Several tokens per call: every wavefront fetches k and q (and KDA's gate vectors) of all its steps once, coalesced
-  // (DK values each per step), and parks them in a region of LDS of its own; a step then reads its lane's rows from
-  // there.  Per-lane global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row): as
-  // many load instructions per 4 steps as the state tile itself takes, and a second set of operand registers to hide
-  // their latency.  No other wavefront reads the region: no barrier.
-  constexpr int kGateSteps = !MULTI ? 1 : DK == 128 ? kMaxRegisterSteps128 : kMaxRegisterSteps64;
-  constexpr bool kGatesInLds = KDA;
-  __shared__ float gate_lds[kGatesInLds ? (DV / 32) * kGateSteps * DK : 1];
-  __shared__ uint32_t kq_lds[(DV / 32) * kGateSteps * DK];  // per (wavefront, step): DK/2 words of k, DK/2 of q
-  float* const my_gates = gate_lds + (kGatesInLds ? wave * kGateSteps * DK : 0);
-  uint32_t* const my_kq = kq_lds + wave * kGateSteps * DK;
-  float2 gate_fetch[kGatesInLds ? kGateSteps : 1];
-  uint32_t k_fetch[kGateSteps], q_fetch[kGateSteps];
+  StepOperands cur, nxt;
+  load_operands<DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, col0);
+  // Every wavefront fetches k and q (and KDA's gate vectors) of all its steps once, coalesced (DK values each per
+  // step), and parks them as fp32 in a region of LDS of its own; a step then reads its lane's rows from there.
+  // Per-lane global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row): as many
+  // load instructions per 4 steps as the state tile itself takes.  No other wavefront reads the region: no barrier.
+  constexpr int kSteps = !MULTI ? 1 : DK == 128 ? kMaxRegisterSteps128 : kMaxRegisterSteps64;
+  constexpr int kVecs = KDA ? 3 : 2;  // k, q, gates
+  static_assert(delta_park_floats<DK, DV, KDA, MULTI>() == (DV / 32) * kSteps * kVecs * Park::kFloats);
+  float* const my_park = park_lds + wave * (kSteps * kVecs * Park::kFloats);
+  float2 gate_fetch[KDA ? kSteps : 1];
+  uint32_t k_fetch[kSteps], q_fetch[kSteps];
   {
     const uint32_t* const ksrc = reinterpret_cast<const uint32_t*>(p.k + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
     const uint32_t* const qsrc = reinterpret_cast<const uint32_t*>(p.q + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
     const size_t step_words = static_cast<size_t>(p.Hk) * DK / 2;
 #pragma unroll
-    for (int t = 0; t < kGateSteps; ++t) {
+    for (int t = 0; t < kSteps; ++t) {
       if (t < T) {
         if constexpr (DK == 128) {
           k_fetch[t] = ksrc[t * step_words + lane];
@@ -161,39 +158,49 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
       }
     }
   }
-  if constexpr (kGatesInLds) {
+  if constexpr (KDA) {
     const float* const src = p.alpha + (static_cast<size_t>(b) * T * p.H + h) * DK;
 #pragma unroll
-    for (int t = 0; t < kGateSteps; ++t) {
+    for (int t = 0; t < kSteps; ++t) {
       if (t < T) {
-        if constexpr (DK == 128)
+        if (EITHER && scalar_gate) {
+          const float a = load_uniform(p.alpha, (static_cast<size_t>(b) * T + t) * p.H + h);
+          gate_fetch[t] = float2{a, a};
+        } else if constexpr (DK == 128) {
           gate_fetch[t] = *reinterpret_cast<const float2*>(src + static_cast<size_t>(t) * p.H * DK + 2 * lane);
-        else
+        } else {
           gate_fetch[t].x = src[static_cast<size_t>(t) * p.H * DK + lane];
+        }
       }
     }
-  } else if constexpr (KDA) {
-    load_gate_vector<DK>(gate_vec, p, static_cast<size_t>(b) * T, h, row0, turn);
   }
   float4 s[RPL];
 #pragma unroll
-  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + 4 * turn) & (RPL - 1)) * DV);
+  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + rot) & (RPL - 1)) * DV);
   __builtin_amdgcn_sched_barrier(0);
   {
+    // where this lane's fetched values go: DK = 128: rows 2*lane, 2*lane+1 of k, of q and of the gates; DK = 64: rows
+    // 2*(lane%32), +1 of k (lower half of the wavefront) or q (upper half), row `lane` of the gates
+    const int pair_row = DK == 128 ? 2 * lane : 2 * (lane & 31);
+    const int at0 = Park::slot(pair_row, rot), at1 = Park::slot(pair_row + 1, rot);
+    const int vec = DK == 128 ? 0 : (lane >> 5) * Park::kFloats;  // DK = 64: the upper half writes into q's vector
 #pragma unroll
-    for (int t = 0; t < kGateSteps; ++t) {
+    for (int t = 0; t < kSteps; ++t) {
       if (t < T) {
+        float* const base = my_park + t * (kVecs * Park::kFloats);
+        base[vec + at0] = bf16_lo(k_fetch[t]);
+        base[vec + at1] = bf16_hi(k_fetch[t]);
         if constexpr (DK == 128) {
-          my_kq[t * DK + lane] = k_fetch[t];
-          my_kq[t * DK + DK / 2 + lane] = q_fetch[t];
-        } else {
-          my_kq[t * DK + lane] = k_fetch[t];  // lanes 32..63 hold q words, which sit right behind the k words
+          base[Park::kFloats + at0] = bf16_lo(q_fetch[t]);
+          base[Park::kFloats + at1] = bf16_hi(q_fetch[t]);
         }
-        if constexpr (kGatesInLds) {
-          if constexpr (DK == 128)
-            *reinterpret_cast<float2*>(my_gates + t * DK + 2 * lane) = gate_fetch[t];
-          else
-            my_gates[t * DK + lane] = gate_fetch[t].x;
+        if constexpr (KDA) {
+          if constexpr (DK == 128) {
+            base[2 * Park::kFloats + at0] = gate_fetch[t].x;
+            base[2 * Park::kFloats + at1] = gate_fetch[t].y;
+          } else {
+            base[2 * Park::kFloats + Park::slot(lane, rot)] = gate_fetch[t].x;
+          }
         }
       }
     }
@@ -202,33 +209,31 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
 
   if (MULTI && n_commit == 0 && p.state_out != p.state_in) {
 #pragma unroll
-    for (int m = 0; m < RPL; ++m) store_state(sout + ((m + 4 * turn) & (RPL - 1)) * DV, s[m]);
+    for (int m = 0; m < RPL; ++m) store_state(sout + ((m + rot) & (RPL - 1)) * DV, s[m]);
   }
 
   for (int t = 0; t < T; ++t) {
     const size_t bt = static_cast<size_t>(b) * T + t;
     if constexpr (MULTI) {
-      if (t + 1 < T) load_operands<DK, DV, KDA, false>(nxt, p, bt + 1, h, hk, row0, col0, turn);
+      if (t + 1 < T) load_operands<DV, KDA>(nxt, p, bt + 1, h, col0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    {
-#pragma unroll
-      for (int j = 0; j < RPL / 4; ++j) {
-        const int word = (row0 + 4 * ((j + turn) & (RPL / 4 - 1))) / 2;
-        cur.k[j] = *reinterpret_cast<const uint2*>(my_kq + t * DK + word);
-        cur.q[j] = *reinterpret_cast<const uint2*>(my_kq + t * DK + DK / 2 + word);
-      }
-    }
+    // this lane's rows of k, q (and the gates) of step t, in register order
+    const float* const mine = my_park + t * (kVecs * Park::kFloats) + r8 * Park::kGroupStride;
     float kf[RPL], qf[RPL];
-    unpack_bf16<RPL>(cur.k, kf);
-    unpack_bf16<RPL>(cur.q, qf);
+#pragma unroll
+    for (int j = 0; j < RPL / 4; ++j) {
+      const float4 kk = *reinterpret_cast<const float4*>(mine + 4 * j);
+      const float4 qq = *reinterpret_cast<const float4*>(mine + Park::kFloats + 4 * j);
+      kf[4 * j] = kk.x, kf[4 * j + 1] = kk.y, kf[4 * j + 2] = kk.z, kf[4 * j + 3] = kk.w;
+      qf[4 * j] = qq.x, qf[4 * j + 1] = qq.y, qf[4 * j + 2] = qq.z, qf[4 * j + 3] = qq.w;
+    }
     const float beta = cur.beta;
 
     if constexpr (KDA) {
 #pragma unroll
       for (int i = 0; i < RPL / 4; ++i) {
-        const float4 a = kGatesInLds ? *reinterpret_cast<const float4*>(my_gates + t * DK + row0 + 4 * ((i + turn) & (RPL / 4 - 1)))
-                                     : gate_vec[i];
+        const float4 a = *reinterpret_cast<const float4*>(mine + 2 * Park::kFloats + 4 * i);
         const float av[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -333,7 +338,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
           x.z *= carry;
           x.w *= carry;
         }
-        store_state(sout + ((m + 4 * turn) & (RPL - 1)) * DV, x);
+        store_state(sout + ((m + rot) & (RPL - 1)) * DV, x);
       }
     }
     if (r8 == 0) {

@@ -35,6 +35,22 @@ __device__ __forceinline__ void merge_items(const MergeParams& m, int first_item
     attn_merge_body(m.swa, item - m.end_fa, d);
 }
 
+// Tile `tile` of a layer's recurrent tiles, KDA's first.  One new token per request: one tile body serves both mixers
+// (a kernel that carried both took 140 registers instead of 107 and ran three wavefronts per SIMD instead of four).
+// A verify pass keeps the two bodies: GDN's carries the decay of several steps as a common factor of the tile.
+template <bool MULTI>
+__device__ __forceinline__ void run_tile(const sa::DeltaParams& kda, const sa::DeltaParams& gdn, int tile, int n_kda, float* park) {
+  const bool is_gdn = tile >= n_kda;
+  if constexpr (!MULTI) {
+    delta_step_body<128, 128, true, false, true>(is_gdn ? gdn : kda, is_gdn ? tile - n_kda : tile, blockIdx.x, park, is_gdn);
+  } else {
+    if (is_gdn)
+      delta_step_body<128, 128, false, true>(gdn, tile - n_kda, blockIdx.x, park);
+    else
+      delta_step_body<128, 128, true, true>(kda, tile, blockIdx.x, park);
+  }
+}
+
 struct LayerParams {
   MergeParams prev;
   sa::AttnParams fa, swa;
@@ -49,6 +65,8 @@ struct LayerParams {
 template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
   __shared__ AttnShared sm;
+  // one region for whichever tile body this workgroup runs (the KDA body needs the larger one)
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI>()];
   const int id = blockIdx.x;
   if (id < p.end_prev) {
     merge_items(p.prev, 2 * id);
@@ -63,10 +81,7 @@ __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
     // the recurrent tiles of both mixers as one list, visited as the stand-alone step kernels visit theirs
     const int tile = interleaved_tile(id - p.end_swa, static_cast<int>(gridDim.x) - p.end_swa);
     const int n_kda = p.end_kda - p.end_swa;
-    if (tile < n_kda)
-      delta_step_body<128, 128, true, MULTI>(p.kda, tile, blockIdx.x);
-    else
-      delta_step_body<128, 128, false, MULTI>(p.gdn, tile - n_kda, blockIdx.x);
+    run_tile<MULTI>(p.kda, p.gdn, tile, n_kda, park);
   }
 }
 
@@ -80,6 +95,7 @@ struct RecurrentLayerParams {
 
 template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI>()];
   if (static_cast<int>(blockIdx.x) < p.end_prev) {
     merge_items(p.prev, 2 * blockIdx.x);
     return;
@@ -87,10 +103,7 @@ __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerPara
   // as the stand-alone step kernels visit their tiles
   const int id = interleaved_tile(static_cast<int>(blockIdx.x) - p.end_prev, static_cast<int>(gridDim.x) - p.end_prev);
   const int n_kda = p.end_kda - p.end_prev;
-  if (id < n_kda)
-    delta_step_body<128, 128, true, MULTI>(p.kda, id, blockIdx.x);
-  else
-    delta_step_body<128, 128, false, MULTI>(p.gdn, id - n_kda, blockIdx.x);
+  run_tile<MULTI>(p.kda, p.gdn, id, n_kda, park);
 }
 
 __global__ __launch_bounds__(256) void layer_merge_kernel(MergeParams p) { merge_items(p, 2 * blockIdx.x); }
@@ -149,7 +162,7 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
     p.end_fa = static_cast<int>(n_prev + n_fa);
     p.end_swa = static_cast<int>(n_prev + n_fa + n_swa);
     p.end_kda = static_cast<int>(n_prev + n_fa + n_swa + n_kda);
-    // The multi-token tile body parks k, q and gate vectors of up to 6 steps in LDS (24 KiB): with the attention body's
+    // The multi-token tile body parks k, q and gate vectors of up to 6 steps in LDS (45 KiB): with the attention body's
     // 32.5 KiB that already limits a CU to the 2 workgroups the K/V stream wants, so no padding is requested.
     if (multi)
       sa::launch(SA_K_LAYER, layer_decode_kernel<true>, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, p);
