@@ -98,7 +98,9 @@ def test_workspace_size_formula():
     assert small > 0 and big >= small and big % (64 * 32 * 130 * 4) == 0
     assert sa.attn_decode_workspace_bytes(64, 1, 32, 8, 128, 32768, 4096) == 0       # one range per (request, KV head)
     assert sa.attn_decode_workspace_bytes(64, 1, 32, 8, 64, 32768, 0) == 0
-
+    # ranges per (request, KV head): at least 16 pages each, 4 or more for full attention when the context allows
+    per_range = lambda n_req, ctx: sa.attn_decode_workspace_bytes(n_req, 1, 32, 8, 128, ctx, 0) // (n_req * 32 * 130 * 4)
+    assert per_range(3, 2048) == 8 and per_range(64, 2048) == 4 and per_range(64, 32768) == 4
 
 def test_kv_append_argument_errors():
     base = dict(k_new=16, v_new=16, kpool=16, vpool=16, n_pages=4, page_table=16, max_pages=4, positions=16, B=1, T=1,
