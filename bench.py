@@ -213,10 +213,10 @@ def main():
                              rec_scale, attn_scale, stream, g)
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
-    cpu = None
+    cpu = cpu_numpy = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(np, torch, gen, rec, q_ring_h[0], kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale,
-                           attn_scale)
+        cpu, cpu_numpy = cpu_baseline(np, torch, gen, rec, q_ring_h[0], kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale,
+                                      attn_scale)
 
     # ---------------------------------------------------------------- 48-layer placement stack (batch 128)
     placement = None
@@ -243,6 +243,7 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "cpu_baseline_numpy": cpu_numpy,
         "placement48": placement,
         "verify": verify,
         "extras": extras,
@@ -605,11 +606,53 @@ def small_stack_graph(torch, steps=20, warmup=3):
 
 
 def cpu_baseline(np, torch, gen, rec, q_h, kpool, vpool, table_h, lens_fa_h, lens_swa_h, rec_scale, attn_scale):
-    """Times the fp64 oracle, as it stands, on a sample of the same step and scales to the full step."""
+    """The oracle, as it stands, timed on the host's cores on a sample of the same step and scaled to the full step:
+    `cpu_baseline` is its fp64 C / OpenMP form (oracle/mixers_omp.c, all cores; admitted by tests/test_oracle_omp.py
+    only while it agrees with the numpy oracle to 1e-12), `cpu_baseline_numpy` the numpy oracle itself."""
     from oracle import kv_layout as kl
     from oracle import mixers as om
+    from oracle import omp
 
-    n_seq, n_groups = 64, 256   # about 15 s of oracle work on the host
+    tbl = torch.from_numpy(table_h).cuda()
+
+    def host_pools(seqs, lens):
+        """The pages of the sampled sequences as compact host pools (physical in-page order) with their page table."""
+        ks, vs, rows, at = [], [], np.full((len(seqs), table_h.shape[1]), -1, dtype=np.int32), 0
+        for i, b in enumerate(seqs):
+            n = (int(lens[b]) + PAGE - 1) // PAGE
+            pages = tbl[b, :n].long()
+            ks.append(kpool[pages].view(torch.int16).cpu().numpy().view(np.uint16))
+            vs.append(vpool[pages].view(torch.int16).cpu().numpy().view(np.uint16))
+            rows[i, :n] = np.arange(at, at + n, dtype=np.int32)
+            at += n
+        return np.concatenate(ks), np.concatenate(vs), rows
+
+    # ---- C / OpenMP twin: both recurrent steps on all 64 sequences, FA and SWA on 32 of the 64 sequences (all KV heads)
+    n_seq_attn = 32
+    t_omp = {}
+    for name, kda, fn in (("gdn", False, omp.gdn_steps), ("kda", True, omp.kda_steps)):
+        p = gen.recurrent_inputs(1002 + kda, B, 1, H, H, DK, DV, kda)
+        S0 = rec[name][1][0].view(B, H, DK, DV).cpu().numpy()
+        t = time.perf_counter()
+        fn(p["q"], p["k"], p["v"], p["alpha"], p["beta"], S0, rec_scale)
+        t_omp[name] = time.perf_counter() - t
+    seqs = list(range(0, B, B // n_seq_attn))
+    for name, lens, window in (("fa", lens_fa_h, 0), ("swa", lens_swa_h, WINDOW)):
+        kph, vph, rows = host_pools(seqs, lens)
+        t = time.perf_counter()
+        omp.attn_decode(q_h[seqs], kph, vph, rows, lens[seqs], window, attn_scale, physical=True)
+        t_omp[name] = (time.perf_counter() - t) * (B / len(seqs))
+        del kph, vph
+    t_step = sum(t_omp.values())
+    fast = {"value": round(B / t_step, 3), "unit": "tokens/s", "cores": omp.threads(), "kind": "oracle",
+            "host_cores_available": len(os.sched_getaffinity(0)),
+            "sample": "fp64 C/OpenMP form of the oracle (plain loops, parallel over (sequence, head)): one GDN and one KDA step "
+                      "on all 64 sequences, FA and SWA on %d of the 64 sequences (all 8 KV heads) scaled to 64" % len(seqs),
+            "seconds_per_full_step_extrapolated": round(t_step, 3),
+            "seconds_by_mixer": {k: round(v, 3) for k, v in t_omp.items()}}
+
+    # ---- the numpy oracle itself
+    n_seq, n_groups = 64, 96   # about 8 s of numpy work on the host
     t_rec = {}
     for name, kda, fn in (("gdn", False, om.gdn_steps), ("kda", True, om.kda_steps)):
         p = gen.recurrent_inputs(1002 + kda, B, 1, H, H, DK, DV, kda)
@@ -618,7 +661,6 @@ def cpu_baseline(np, torch, gen, rec, q_h, kpool, vpool, table_h, lens_fa_h, len
         fn(p["q"][:n_seq], p["k"][:n_seq], p["v"][:n_seq], p["alpha"][:n_seq], p["beta"][:n_seq], S0, rec_scale)
         t_rec[name] = (time.perf_counter() - t) * (B / n_seq)
     t_attn = {}
-    tbl = torch.from_numpy(table_h).cuda()
     rng = np.random.default_rng(77)
     for name, lens, window in (("fa", lens_fa_h, 0), ("swa", lens_swa_h, WINDOW)):
         total = 0.0
@@ -642,13 +684,13 @@ def cpu_baseline(np, torch, gen, rec, q_h, kpool, vpool, table_h, lens_fa_h, len
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         threads = 1
-    return {"value": round(B / t_step, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "host_cores_available": len(os.sched_getaffinity(0)),
+    slow = {"value": round(B / t_step, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": "numpy fp64 oracle timed on %d of 64 sequences (all 32 heads) for one GDN and one KDA step and on "
                       "%d of 512 (sequence, KV head) groups (4 query heads each) for FA and for SWA, each scaled to the "
-                      "full step; einsum parts run on one thread, matrix-vector products on the BLAS threads counted "
+                      "full step; its einsum parts run on one thread, only matrix-vector products use the BLAS threads counted "
                       "in `cores`" % (n_seq, n_groups),
             "seconds_per_full_step_extrapolated": round(t_step, 2)}
+    return fast, slow
 
 
 if __name__ == "__main__":
