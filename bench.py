@@ -29,9 +29,30 @@ HQ, HKV, D, PAGE = 32, 8, 128, 16
 CTX, WINDOW = 32768, 4096
 N_STATE_SETS = 8      # 8 x 128 MiB per recurrent mixer: the working set exceeds the 256 MB last-level cache
 N_RING = 8            # distinct pre-staged operand sets
-# HBM bytes per launch of the full-attention split kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# scaled by the copy-kernel calibration (profiles/batch64_step_all_kernels_hbm_bytes.txt).
-FA_SPLIT_TRAFFIC_BYTES = 8599005184
+# HBM bytes per launch of the full-attention split kernel (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
+# copy-kernel calibration) are read at run time from this summary, together with the hash of the sources it was taken on.
+TRAFFIC_PROFILE = os.path.join("profiles", "batch64_step_all_kernels_hbm_bytes.txt")
+
+
+def profiled_traffic():
+    """(bytes per launch or None, where the figure comes from).  The summary carries two `name = value` lines:
+    `fa_split_traffic_bytes` and `library_sources_sha16` (the sources the counters were collected on)."""
+    from paper_2604_19877_amd.build import source_sha16
+    src = {"file": TRAFFIC_PROFILE, "library_sources_sha16_now": source_sha16()}
+    try:
+        vals = {}
+        with open(os.path.join(ROOT, TRAFFIC_PROFILE)) as f:
+            for line in f:
+                name, sep, val = line.partition("=")
+                if sep and name.strip() in ("fa_split_traffic_bytes", "library_sources_sha16"):
+                    vals[name.strip()] = val.strip()
+        traffic = int(vals["fa_split_traffic_bytes"].replace(",", ""))
+        src["library_sources_sha16_when_profiled"] = vals.get("library_sources_sha16")
+        src["same_sources"] = src["library_sources_sha16_when_profiled"] == src["library_sources_sha16_now"]
+        return traffic, src
+    except (OSError, KeyError, ValueError) as e:
+        src["error"] = "%s: %s" % (type(e).__name__, e)
+        return None, src
 
 
 def parse_args():
@@ -51,6 +72,9 @@ def parse_args():
                          "their decode speedup over the all-FA preset, mixers only")
     ap.add_argument("--prefill", type=int, default=0, metavar="T",
                     help="only run the chunk-parallel recurrent kernels over T tokens per sequence (batch 64) and print their times")
+    ap.add_argument("--literal-configs", action="store_true",
+                    help="also run 256 GDN and 256 KDA steps on one 128 MiB state set (BASELINE configs 2 and 3 as written) when "
+                         "--no-extras is given (profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the plain 1 GiB copy kernel 3 times after the timed region (counter calibration)")
     return ap.parse_args()
@@ -196,9 +220,10 @@ def main():
     if copy_entry:
         kernels["copy_1GiB"] = copy_entry
     dom = kernels["attn_split_fa"]
+    traffic, traffic_source = profiled_traffic()
     roofline = {"kernel": "attn_split_kernel (full attention, 64 x 32768 tokens)", "bound": "hbm",
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_hbm_peak"],
-                "traffic": FA_SPLIT_TRAFFIC_BYTES}
+                "traffic": traffic, "traffic_source": traffic_source, "algorithmic_bytes": dom["alg_bytes"]}
 
     # ---------------------------------------------------------------- 4-token verify step of every mixer
     verify = None
@@ -211,6 +236,19 @@ def main():
     if not args.no_extras:
         extras = extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages, lens_swa, lens_swa_h,
                              rec_scale, attn_scale, stream, g)
+
+    if extras:
+        # what bare streams of the same access patterns reach on this machine in this run (no arithmetic): the practical ceiling
+        roofline["ceiling"] = {
+            "read_stream_GBps": extras["state_tiles_read_only_b64"]["GBps"],
+            "read_write_stream_GBps": extras["state_tiles_read_write_only_b64"]["GBps"],
+            "tile_copy_1GiB_GBps": kernels.get("copy_1GiB", {}).get("GBps"),
+            "note": "sa_stream_tiles over 128 MiB of 64 KiB tiles (read only / read, scale, write back) and sa_copy_bytes "
+                    "over 1 GiB (64 KiB tiles, non-temporal), kernel-attached events; frac_of_read_stream = achieved / read_stream"}
+        roofline["ceiling"]["frac_of_read_stream"] = round(dom["GBps"] / roofline["ceiling"]["read_stream_GBps"], 4)
+
+    if extras is None and args.literal_configs:
+        extras = literal_state_set_cases(torch, sa, gen, dev, rec_scale, stream, g)
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = cpu_numpy = None
@@ -228,6 +266,10 @@ def main():
         scattered = placement_stack(torch, sa, stream, page_scatter="global")
         placement["pages_shuffled_over_the_whole_pool"] = {k: scattered[k] for k in ("ms_per_step", "tokens_per_s", "frac_hbm_peak")}
         placement["launch_bound_case"] = small_stack_graph(torch)
+        torch.cuda.empty_cache()
+        # Section 4 "Cost model" on this GPU, mixers only: 1/throughput = sum_m c_m n_m fitted on 7 allocations (the four
+        # pure stacks and three mixed ones); --cost-table fits 14
+        placement["cost_model"] = cost_table(np, torch, gen, stream, steps=4, allocations=SHORT_ALLOCATIONS)
 
     line = {
         "metric": "mixer decode tokens/s at batch 64 + % of MI355X peak HBM GB/s",
@@ -347,6 +389,7 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
                         "GBps": round(passes * tile_bytes / (avg * 1e-3) / 1e9, 1),
                         "frac_hbm_peak": round(passes * tile_bytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
             del states
+    res.update(literal_state_set_cases(torch, sa, gen, dev, rec_scale, stream, g))
     # whole-block step: convolution + SiLU, L2 norm, gates, state update and gated RMS norm in one launch
     for name, kda, fn, kid in (("gdn", False, sa.gdn_block_decode, sa.SA_K_GDN_BLOCK), ("kda", True, sa.kda_block_decode, sa.SA_K_KDA_BLOCK)):
         taps, sets = 4, 8
@@ -412,6 +455,32 @@ def extra_cases(np, torch, sa, gen, dev, kpool, vpool, n_pages, table, max_pages
     return res
 
 
+def literal_state_set_cases(torch, sa, gen, dev, rec_scale, stream, g, n_steps=256):
+    """BASELINE configs 2 and 3 to the letter: 256 consecutive steps on ONE state set (128 MiB, which fits the 256 MB
+    last-level cache) with fresh operands per step, beside the rotation over 8 sets that the headline figures use."""
+    res = {}
+    for name, kda, fn, kid in (("gdn", False, sa.gdn_decode_step, sa.SA_K_GDN), ("kda", True, sa.kda_decode_step, sa.SA_K_KDA)):
+        ring = [{n: dev(a) for n, a in gen.recurrent_inputs(1850 + 7 * i + kda, B, 1, H, H, DK, DV, kda).items()} for i in range(N_RING)]
+        state = torch.empty((B * H, DK, DV), dtype=torch.float32, device="cuda")
+        state.normal_(0.0, 0.02, generator=g)
+        out = torch.empty((B, 1, H, DV), dtype=torch.float32, device="cuda")
+        sa.sa_prof_enable(True)
+        for i in range(n_steps):
+            x = ring[i % N_RING]
+            fn(x["q"], x["k"], x["v"], x["alpha"], x["beta"], state, state, out, None, None, 0, B, 1, H, H, DK, DV, rec_scale, 1, stream)
+        torch.cuda.synchronize()
+        sa.sa_prof_enable(False)
+        _, _, ms = sa.sa_prof_read(kid, n_steps)
+        avg = sum(ms[8:]) / (len(ms) - 8)
+        nbytes = 2 * B * H * DK * DV * 4 + B * (2 * H * DK * 2 + H * DV * 2 + H * DV * 4 + H * 4) + B * H * (DK if kda else 1) * 4
+        res["%s_b64_one_state_set_256_steps" % name] = {
+            "avg_us": round(avg * 1e3, 2), "min_us": round(min(ms) * 1e3, 2), "tokens_per_s": round(B / (avg * 1e-3), 1),
+            "frac_hbm_peak_if_all_bytes_came_from_hbm": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "note": "the same 128 MiB of states re-stepped while it may still sit in the 256 MB last-level cache"}
+        del state, ring
+    return res
+
+
 def chunk_cases(torch, sa, T, rec_scale, stream, g, reps=6):
     """gdn_chunk_steps / kda_chunk_steps over T tokens for each of 64 sequences x 32 heads; inputs drawn on the
     device with the recipe's distributions, states rotating over 4 sets."""
@@ -442,13 +511,17 @@ def chunk_cases(torch, sa, T, rec_scale, stream, g, reps=6):
     return res
 
 
-def cost_table(np, torch, gen, stream, batch=32, ctx=16384, steps=6):
+SHORT_ALLOCATIONS = [(48, 0, 0, 0), (0, 48, 0, 0), (0, 0, 48, 0), (0, 0, 0, 48), (24, 24, 0, 0), (12, 12, 12, 12), (0, 16, 16, 16)]
+
+
+def cost_table(np, torch, gen, stream, batch=32, ctx=16384, steps=6, allocations=None):
     """The paper's linear cost model (Section 4, "Cost model": 1/throughput = sum over mixers of c_m * n_m,
     fitted on measured placements) for the mixers-only stack on this GPU: all requests of a batch share one
     placement, as in the paper's single-preset measurements."""
     from paper_2604_19877_amd.workloads import PlacementWorkload
-    allocations = [(48, 0, 0, 0), (0, 48, 0, 0), (0, 0, 48, 0), (0, 0, 0, 48), (24, 24, 0, 0), (24, 0, 24, 0), (24, 0, 0, 24),
-                   (12, 12, 12, 12), (0, 16, 16, 16), (6, 30, 6, 6), (3, 25, 4, 16), (0, 10, 5, 33), (12, 26, 6, 4), (0, 30, 5, 13)]
+    if allocations is None:
+        allocations = [(48, 0, 0, 0), (0, 48, 0, 0), (0, 0, 48, 0), (0, 0, 0, 48), (24, 24, 0, 0), (24, 0, 24, 0), (24, 0, 0, 24),
+                       (12, 12, 12, 12), (0, 16, 16, 16), (6, 30, 6, 6), (3, 25, 4, 16), (0, 10, 5, 33), (12, 26, 6, 4), (0, 30, 5, 13)]
     rows, times = [], []
     for i, (f, s_, k, g_) in enumerate(allocations):
         placement = gen.placement_string(6000 + i, 48, {"F": f, "S": s_, "K": k, "G": g_})

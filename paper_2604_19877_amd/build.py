@@ -21,6 +21,18 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+def source_sha16() -> str:
+    """First 16 hex digits of the SHA-256 over the library's sources (csrc/*.hip, csrc/*.h, include/samixers.h, in name
+    order): profile summaries record it, so that a reader can tell whether they describe the kernels of this tree."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    for path in files + [os.path.join(ROOT, "include", "samixers.h")]:
+        with open(path, "rb") as f:
+            h.update(os.path.basename(path).encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
@@ -47,3 +59,4 @@ def build(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     build(verbose=True)
+    print("library sources sha16", source_sha16())

@@ -82,10 +82,27 @@ sa_status sa_prof_read(int kernel, int* n_launches, float* total_ms, float* ms_e
 
 namespace {
 
-// Grid-stride copy, 16 bytes per lane per iteration.
+// Grid-stride copy, 16 bytes per lane per iteration (the tail of sa_copy_bytes, and the state conversions).
 __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
   size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
   for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Copy in 64 KiB tiles, one per workgroup, the way the recurrent step moves a state tile: all 16 non-temporal 16-byte
+// loads of a lane are requested before the first store, rows are walked from a start that differs between neighbouring
+// workgroups, and the tile list is visited in four interleaved quarters.  This is the copy the bandwidth figures are
+// compared with (a plain grid-stride copy reaches 4.6 TB/s on MI355X, less than any kernel of the library).
+__global__ __launch_bounds__(256) void copy_tiles_kernel(const float* __restrict__ src, float* __restrict__ dst) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c8 = lane & 7, r8 = lane >> 3;
+  const size_t tile = static_cast<size_t>(interleaved_tile(blockIdx.x, gridDim.x));
+  const int turn4 = 4 * (blockIdx.x & 3);
+  const size_t at = tile * (128 * 128) + (r8 * 16) * 128 + wave * 32 + c8 * 4;
+  float4 s[16];
+#pragma unroll
+  for (int m = 0; m < 16; ++m) s[m] = load_state(src + at + ((m + turn4) & 15) * 128);
+#pragma unroll
+  for (int m = 0; m < 16; ++m) store_state(dst + at + ((m + turn4) & 15) * 128, s[m]);
 }
 
 }  // namespace
@@ -95,12 +112,20 @@ extern "C" sa_status sa_copy_bytes(const void* src, void* dst, size_t n_bytes, v
   SA_REQUIRE(sa::aligned(src, 16) && sa::aligned(dst, 16) && n_bytes % 16 == 0, SA_EINVAL,
              "sa_copy_bytes: pointers and size must be multiples of 16 bytes");
   if (n_bytes == 0) return SA_OK;
-  size_t n16 = n_bytes / 16;
-  size_t blocks = (n16 + 255) / 256;
-  if (blocks > 256 * 16) blocks = 256 * 16;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  sa::launch(SA_K_COPY, copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, static_cast<const uint4*>(src),
-             static_cast<uint4*>(dst), n16);
+  constexpr size_t kTile = 64 * 1024;
+  const size_t n_tiles = n_bytes / kTile;
+  SA_REQUIRE(n_tiles <= 0x7fffffffULL, SA_EUNSUPPORTED, "sa_copy_bytes: more than 2^31 tiles of 64 KiB");
+  if (n_tiles)
+    sa::launch(SA_K_COPY, copy_tiles_kernel, dim3(static_cast<unsigned>(n_tiles)), dim3(256), 0, s, static_cast<const float*>(src),
+               static_cast<float*>(dst));
+  const size_t done = n_tiles * kTile, n16 = (n_bytes - done) / 16;
+  if (n16) {
+    size_t blocks = (n16 + 255) / 256;
+    hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
+                       reinterpret_cast<const uint4*>(static_cast<const char*>(src) + done),
+                       reinterpret_cast<uint4*>(static_cast<char*>(dst) + done), n16);
+  }
   return sa::check_launch("sa_copy_bytes");
 }
 
