@@ -318,43 +318,75 @@ def test_same_placement_for_all_requests_and_empty_batch():
     sa.placement_plan_destroy(empty)
 
 
-def test_full_size_stack_batch128_ctx16384_sampled():
-    """48 layers, batch 128, 16384-token contexts, three placements (about 126 GiB of KV cache and
-    state): one placement_decode step in the configuration the benchmark times; the oracle checks two
-    seeded requests of every placement through all 48 layers (all heads of a recurrent layer, one seeded
+def test_full_size_stack_batch128_ctx16384():
+    """BASELINE config 5: 48 layers, batch 128, 16384-token contexts, three placements (about 126 GiB of KV cache and
+    state): one placement_decode step in the configuration the benchmark times.  Against the fp64 C form of the oracle
+    (admitted at 1e-12 from the numpy oracle by tests/test_oracle_omp.py): every recurrent tile of every layer (all 128
+    requests), and every query head of four seeded requests per placement on every attention layer.  Against the numpy
+    oracle itself: two of those requests per placement through all 48 layers (all heads of a recurrent layer, one seeded
     query head of an attention layer)."""
+    from oracle import omp
     from paper_2604_19877_amd.workloads import PlacementWorkload, fetch_logical_kv
     w = PlacementWorkload(B=128, L=48, ctx=16384, window=4096, T=1, seed=5000)
     try:
         rng = np.random.default_rng(6)
-        requests = []
+        wide, requests = [], []
         for p in range(3):
-            requests += [int(r) for r in rng.choice(np.flatnonzero(w.pid == p), size=2, replace=False)]
-        before = {}
-        for l in range(w.L):
-            for r in requests:
-                if w.mixer[l, r] in "KG":
-                    slot = int(w.host[l]["slot"][r])
-                    before[(l, r)] = w.layers[l]["state"].view(-1, H, DK, DV)[slot].cpu().numpy()
+            chosen = [int(r) for r in rng.choice(np.flatnonzero(w.pid == p), size=4, replace=False)]
+            wide += chosen
+            requests += chosen[:2]
+        before = [w.layers[l]["state"].view(-1, H, DK, DV).cpu().numpy() for l in range(w.L)]
         w.step()
         torch.cuda.synchronize()
         seen = set()
         for l in range(w.L):
             hl = w.host[l]
+            got_l = w.layers[l]["out"].cpu().numpy()
+            got_state = w.layers[l]["state"].view(-1, H, DK, DV).cpu().numpy()
+            assert np.isfinite(got_l).all()
+            # every recurrent tile of the layer
+            for m, fn, gate in (("K", omp.kda_steps, "alpha_vec"), ("G", omp.gdn_steps, "alpha_scalar")):
+                rows = np.flatnonzero(w.mixer[l] == m)
+                if len(rows) == 0:
+                    continue
+                slots = hl["slot"][rows]
+                o_ref, s_ref = fn(hl["q"][rows], hl["k"][rows], hl["v"][rows], hl[gate][rows], hl["beta"][rows], before[l][slots],
+                                  w.rec_scale)
+                for i, r in enumerate(rows):
+                    assert rel_err(got_l[r], o_ref[i]) <= OUT_TOL, (l, r, m)
+                    assert rel_err(got_state[slots[i]], s_ref[i]) <= STATE_TOL, (l, r, m)
+            # every query head of the widely sampled requests on the attention mixers of the layer
+            for m in "FS":
+                rows = [r for r in wide if w.mixer[l, r] == m]
+                if not rows:
+                    continue
+                first = 0 if m == "F" else (w.ctx - w.window) // 16
+                n = w.max_pages - first
+                table = np.full((len(rows), w.max_pages), -1, dtype=np.int32)
+                ks, vs = [], []
+                for i, r in enumerate(rows):
+                    pages = torch.as_tensor(hl["page_table"][r, first:], device="cuda").long()
+                    ks.append(w.kpool[pages].view(torch.int16).cpu().numpy().view(np.uint16))
+                    vs.append(w.vpool[pages].view(torch.int16).cpu().numpy().view(np.uint16))
+                    table[i, first:] = np.arange(i * n, (i + 1) * n)
+                ref = omp.attn_decode(hl["q"][rows], np.concatenate(ks), np.concatenate(vs), table, np.full(len(rows), w.ctx, dtype=np.int32),
+                                      w.window if m == "S" else 0, w.attn_scale, physical=True)
+                for i, r in enumerate(rows):
+                    for h in range(HQ):
+                        assert rel_err(got_l[r][:, h], ref[i][:, h]) <= OUT_TOL, (l, r, m, h)
+            # the numpy oracle on its sample
             for r in requests:
                 m = str(w.mixer[l, r])
                 seen.add(m)
-                got = w.layers[l]["out"][r].cpu().numpy()
-                assert np.isfinite(got).all()
+                got = got_l[r]
                 if m in "KG":
                     fn = om.kda_steps if m == "K" else om.gdn_steps
                     a = hl["alpha_vec"] if m == "K" else hl["alpha_scalar"]
                     sl = slice(r, r + 1)
-                    o_ref, s_ref = fn(hl["q"][sl], hl["k"][sl], hl["v"][sl], a[sl], hl["beta"][sl], before[(l, r)][None], w.rec_scale)
                     slot = int(hl["slot"][r])
-                    got_s = w.layers[l]["state"].view(-1, H, DK, DV)[slot].cpu().numpy()
+                    o_ref, s_ref = fn(hl["q"][sl], hl["k"][sl], hl["v"][sl], a[sl], hl["beta"][sl], before[l][slot][None], w.rec_scale)
                     assert rel_err(got, o_ref[0]) <= OUT_TOL, (l, r, m)
-                    assert rel_err(got_s, s_ref[0]) <= STATE_TOL, (l, r, m)
+                    assert rel_err(got_state[slot], s_ref[0]) <= STATE_TOL, (l, r, m)
                 else:
                     window = w.window if m == "S" else 0
                     first = 0 if m == "F" else (w.ctx - w.window) // 16

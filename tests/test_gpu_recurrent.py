@@ -77,26 +77,43 @@ def test_four_tokens_per_call_256_tokens(kda, tiny):
     assert rel_err(S, S_ref) <= STATE_TOL
 
 
+def per_tile_rel_err(got, ref, head_axis):
+    """max_i |g_i - r_i| / (|r_i| + rms(r)) per (sequence, head), the metric of gpu_util.rel_err tile by tile."""
+    got = np.moveaxis(np.asarray(got, dtype=np.float64), head_axis, 1)
+    ref = np.moveaxis(np.asarray(ref, dtype=np.float64), head_axis, 1)
+    B, H = ref.shape[:2]
+    got, ref = got.reshape(B, H, -1), ref.reshape(B, H, -1)
+    rms = np.sqrt(np.mean(ref ** 2, axis=2, keepdims=True))
+    return np.max(np.abs(got - ref) / (np.abs(ref) + rms), axis=2)
+
+
 @pytest.mark.parametrize("kda,B", [(False, 64), (True, 64), (True, 256)])
-def test_full_shape_256_steps_sampled_tiles(kda, B):
-    """15B-class shape (32 heads, 128x128 fp32 states ~ N(0, 0.02^2)), 256 consecutive steps on the
-    GPU for every tile; the oracle follows a seeded sample of tiles (tiles are independent)."""
-    H, dk, dv = 32, 128, 128
-    steps = 256 if B == 64 else 32
+def test_full_shape_256_steps_every_tile(kda, B):
+    """BASELINE configs 2 and 3 (and 3's batch 256): 15B-class shape (32 heads, 128x128 fp32 states ~ N(0, 0.02^2)), 256
+    consecutive steps on the GPU.  Every tile and every step is checked against the oracle's fp64 C form (plain loops,
+    admitted at 1e-12 from the numpy oracle by tests/test_oracle_omp.py); a seeded sample of tiles is also followed by the
+    numpy oracle itself, which the C form must match on those tiles at this size too."""
+    from oracle import omp
+    H, dk, dv, steps = 32, 128, 128, 256
     p = stepwise_inputs(1002 + kda + B, steps, B, 1, H, H, dk, dv, kda)
     S0 = gen.recurrent_state(7, B * H, dk, dv).reshape(B, H, dk, dv)
     scale = dk ** -0.5
     o, S = run_gpu(kda, p, S0, B, 1, H, H, dk, dv, scale)
     assert np.isfinite(o).all() and np.isfinite(S).all()
-    rng = np.random.default_rng(5)
-    tiles = [(int(rng.integers(B)), int(rng.integers(H))) for _ in range(254)] + [(0, 0), (B - 1, H - 1)]
     seq = {n: as_sequence(p, n) for n in p}
+    o_all, S_all = (omp.kda_steps if kda else omp.gdn_steps)(seq["q"], seq["k"], seq["v"], seq["alpha"], seq["beta"], S0, scale)
+    err_o, err_s = per_tile_rel_err(o, o_all, 2), per_tile_rel_err(S, S_all, 1)
+    assert err_o.max() <= OUT_TOL, np.unravel_index(err_o.argmax(), err_o.shape)
+    assert err_s.max() <= STATE_TOL, np.unravel_index(err_s.argmax(), err_s.shape)
+    rng = np.random.default_rng(5)
+    tiles = [(int(rng.integers(B)), int(rng.integers(H))) for _ in range(30)] + [(0, 0), (B - 1, H - 1)]
     for (b, h) in tiles:
         sl = (slice(b, b + 1), slice(None), slice(h, h + 1))
         o_ref, S_ref = FN[kda][1](seq["q"][sl], seq["k"][sl], seq["v"][sl], seq["alpha"][sl], seq["beta"][sl],
                                   S0[b:b + 1, h:h + 1], scale)
         assert rel_err(o[b, :, h], o_ref[0, :, 0]) <= OUT_TOL, (b, h)
         assert rel_err(S[b, h], S_ref[0, 0]) <= STATE_TOL, (b, h)
+        assert np.max(np.abs(o_all[b, :, h] - o_ref[0, :, 0])) <= 1e-12 and np.max(np.abs(S_all[b, h] - S_ref[0, 0])) <= 1e-12
 
 
 @pytest.mark.parametrize("kda", [False, True])
