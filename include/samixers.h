@@ -286,6 +286,8 @@ size_t placement_workspace_bytes(const sa_plan* plan, const sa_shapes* shapes, i
  * steps to the rounding order of their sums (a tile's rows are added in an order that depends on the workgroup's place
  * in the grid; a given launch is run-to-run deterministic).  Every layer's output is complete in stream order when
  * the call's last launch has run.
+ * Layers may share one output buffer or use one each: where the outputs of two consecutive layers overlap, the
+ * earlier layer's partial results are merged by a launch of their own instead of riding on the later layer's launch.
  * Recurrent layers update their states in place, by all T steps or by each request's n_commit_rows.
  * workspace: device memory, 256-byte aligned, at least placement_workspace_bytes(); SA_EWORKSPACE if too small. */
 sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io, const sa_shapes* shapes, int T, int window,

@@ -63,8 +63,14 @@ struct ChunkParams {
 constexpr int kD = 128;          // dk = dv
 constexpr int kC = 16;           // tokens per chunk
 constexpr int kTokRowB = 272;    // bytes of one token row of K or Q in LDS (256 + 16: spreads the rows over banks)
-constexpr int kChRowB = 40;      // bytes of one key-channel row (16 tokens, 32 + 8) of the channel-major K copy
-constexpr int kStageB = 2 * kC * kTokRowB + kD * kChRowB;  // one chunk's K, Q and transposed K
+// Channel-major copies of K (16 tokens = 32 bytes per key channel): rows 48 bytes apart plus 8 bytes after every 8
+// channels.  They are written 2 bytes at a time by lanes that hold channels 8 apart (each thread stages 8 channels of one
+// token) and read 8 bytes at a time by lanes on consecutive channels; with plain 40-byte rows the 16 writing lanes of a
+// token fell on 4 LDS banks, with this spacing writers and readers both spread over all banks.
+constexpr int kChRowB = 48, kChGroupPadB = 8;
+constexpr int kChnB = kD * kChRowB + (kD / 8) * kChGroupPadB;   // bytes of one channel-major copy
+__device__ __forceinline__ int chn_row(int channel) { return channel * kChRowB + (channel >> 3) * kChGroupPadB; }
+constexpr int kStageB = 2 * kC * kTokRowB + kChnB;  // one chunk's K, Q and transposed K
 constexpr int kMatRow = 20;      // floats per row of the per-wavefront 16x16 matrices (16 + 4)
 constexpr int kWaveB = (2 * kC * kMatRow + kC * 4 + 64) * 4;  // A (off-diagonal blocks), M, diagonal blocks of A, dump slots
 
@@ -230,7 +236,11 @@ __device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p,
   f.beta = n <= lim ? bt : 0.f;
 }
 
-__global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
+// ONE: the call is a single chunk (T <= 16, a verify pass): nothing is prefetched for a next chunk and one staging
+// buffer is enough, which leaves registers and LDS for a third wavefront per SIMD (8 tokens at batch 64: 51 us
+// against 54 us; a kernel of many chunks forced to the same register budget spills and runs 60 % slower).
+template <bool ONE>
+__global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int r = blockIdx.x / p.H;
   const int h = blockIdx.x - r * p.H;
@@ -245,7 +255,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
   const int col = wave * 32 + 2 * n;
   const size_t row0 = static_cast<size_t>(b) * p.T;
 
-  float* const wave_mat = reinterpret_cast<float*>(lds + 2 * kStageB + wave * kWaveB);
+  float* const wave_mat = reinterpret_cast<float*>(lds + (ONE ? 1 : 2) * kStageB + wave * kWaveB);
   float* const a_off = wave_mat;                      // [16][kMatRow]: beta_t g(t,i) k_t.k_i for i in an earlier 4-row group
   float* const m_low = wave_mat + kC * kMatRow;       // [16][kMatRow]: g(t,i) q_t.k_i for i <= t
   float* const a_dia = wave_mat + 2 * kC * kMatRow;   // [16][4]: the same products for i in t's own group, i < t
@@ -277,15 +287,15 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
   // instead of into 64 multiplications per lane, and the factor is multiplied in once it falls below 2^-96
   // (and wherever the state is stored).  The factor is the same for the whole workgroup.
   float c_log = 0.f;
-  const int n_chunks = (p.T + kC - 1) / kC;
+  const int n_chunks = ONE ? 1 : (p.T + kC - 1) / kC;
   for (int ch = 0; ch < n_chunks; ++ch) {
     const int t0 = ch * kC;
     const int n_keep = n_commit - t0;  // tokens of this chunk that the stored state includes, if it is stored here
     if (n_keep == 0 && n_commit < p.T && (t0 > 0 || sout != sin)) store_tile(S, sout, lane_off, exp2f(c_log));
-    unsigned char* const stage = lds + (ch & 1) * kStageB;
+    unsigned char* const stage = lds + (ONE ? 0 : (ch & 1) * kStageB);
     unsigned char* const k_tok = stage;                       // [16 tokens][kTokRowB]
     unsigned char* const q_tok = stage + kC * kTokRowB;
-    unsigned char* const k_chn = stage + 2 * kC * kTokRowB;   // [128 channels][kChRowB]
+    unsigned char* const k_chn = stage + 2 * kC * kTokRowB;   // 128 channels, channel c at chn_row(c)
     {
       const int tok = tid >> 4, c8 = (tid & 15) * 8;
       *reinterpret_cast<u32x4*>(k_tok + tok * kTokRowB + c8 * 2) = cur.kst;
@@ -293,13 +303,13 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const uint32_t w = cur.kst[e >> 1];
-        *reinterpret_cast<uint16_t*>(k_chn + (c8 + e) * kChRowB + tok * 2) = static_cast<uint16_t>((e & 1) ? (w >> 16) : (w & 0xffffu));
+        *reinterpret_cast<uint16_t*>(k_chn + chn_row(c8 + e) + tok * 2) = static_cast<uint16_t>((e & 1) ? (w >> 16) : (w & 0xffffu));
       }
     }
     __syncthreads();
     // The buffer written above was last read two chunks ago, and every wavefront has passed the
     // previous chunk's barrier since, so one barrier per chunk is enough.
-    if (ch + 1 < n_chunks) {
+    if (!ONE && ch + 1 < n_chunks) {
       // An opaque copy of the next chunk's first token keeps the address arithmetic here, in scalar registers.
       int t_next = t0 + kC;
       asm volatile("" : "+s"(t_next));
@@ -407,7 +417,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
       }
 #pragma unroll
       for (int rt = 0; rt < 8; ++rt) {
-        const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g);
+        const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + chn_row(16 * rt + n) + 8 * g);
         f32x4 acc[2];
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
@@ -447,13 +457,13 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
     }
 #pragma unroll
     for (int rt = 0; rt < 8; ++rt) {
-      const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + (16 * rt + n) * kChRowB + 8 * g);
+      const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + chn_row(16 * rt + n) + 8 * g);
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         S[rt][c] = mfma_two_terms(kt, ds[c], S[rt][c]);
       }
     }
-    cur = nxt;
+    if (!ONE) cur = nxt;
     // The per-wavefront matrices are rewritten in the next chunk only after this chunk's reads (program order).
   }
 
@@ -481,7 +491,7 @@ __global__ __launch_bounds__(256, 2) void gdn_chunk_kernel(ChunkParams p) {
 // channel-major for K^T Delta; barrier; (3) each wavefront consumes them as in the GDN kernel.
 constexpr int kTabRow = kD;                                // floats per token row of the P and 1/P tables
 constexpr int kKdaTok = 6 * kC * kTokRowB;                 // Khat, Ktil, Qhat x (hi, lo), token-major
-constexpr int kKdaChn = 2 * kD * kChRowB;                  // Kend (hi, lo), channel-major
+constexpr int kKdaChn = 2 * kChnB;                  // Kend (hi, lo), channel-major
 constexpr int kKdaTab = kC * kTabRow * 4;                  // P
 constexpr int kKdaMisc = kD * 4 + 16;                      // P at the pass's last token per channel; token limits of 2 wavefronts
 constexpr int kKdaLds = kKdaTok + kKdaChn + kKdaTab + kKdaMisc + 4 * kWaveB;
@@ -547,7 +557,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
   // Token-major operand arrays in the order Khat hi, Khat lo, Ktil hi, Ktil lo, Qhat hi, Qhat lo.
   unsigned char* const tok_arr = lds;
   unsigned char* const kend_hi = lds + kKdaTok;
-  unsigned char* const kend_lo = kend_hi + kD * kChRowB;
+  unsigned char* const kend_lo = kend_hi + kChnB;
   float* const p_tab = reinterpret_cast<float*>(lds + kKdaTok + kKdaChn);   // [16][128] P_t per channel
   float* const p_end = p_tab + kC * kTabRow;                               // [128] P at the last token of the pass
   int* const limit = reinterpret_cast<int*>(p_end + kD);                    // [2] first token the channels of a wavefront refuse
@@ -645,7 +655,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
           const uint32_t hi[4] = {x.hi[0], x.hi[1], y.hi[0], y.hi[1]}, lo[4] = {x.lo[0], x.lo[1], y.lo[0], y.lo[1]};
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const int at = (c8 + e) * kChRowB + tok * 2;
+            const int at = chn_row(c8 + e) + tok * 2;
             *reinterpret_cast<uint16_t*>(kend_hi + at) = static_cast<uint16_t>((e & 1) ? (hi[e >> 1] >> 16) : (hi[e >> 1] & 0xffffu));
             *reinterpret_cast<uint16_t*>(kend_lo + at) = static_cast<uint16_t>((e & 1) ? (lo[e >> 1] >> 16) : (lo[e >> 1] & 0xffffu));
           }
@@ -736,7 +746,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
       Split4x2 ds[2] = {split2(rhs[0]), split2(rhs[1])};
 #pragma unroll
       for (int rt = 0; rt < 8; ++rt) {
-        const int at = (16 * rt + n) * kChRowB + 8 * g;
+        const int at = chn_row(16 * rt + n) + 8 * g;
         const u32x2 e_hi = *reinterpret_cast<const u32x2*>(kend_hi + at);
         const s16x4 e_lo = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(kend_lo + at));
         const f32x4 row_scale = *reinterpret_cast<const f32x4*>(p_end + 16 * rt + 4 * g);
@@ -789,7 +799,10 @@ sa_status chunk_launch(bool dry_run, const char* name, const void* q, const void
   if (KDA) {
     sa::launch(SA_K_KDA_CHUNK, kda_chunk_kernel, grid, dim3(256), kKdaLds, s, p);
   } else {
-    sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel, grid, dim3(256), 2 * kStageB + 4 * kWaveB, s, p);
+    if (T <= kC)
+      sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel<true>, grid, dim3(256), kStageB + 4 * kWaveB, s, p);
+    else
+      sa::launch(SA_K_GDN_CHUNK, gdn_chunk_kernel<false>, grid, dim3(256), 2 * kStageB + 4 * kWaveB, s, p);
   }
   return sa::check_launch(name);
 }

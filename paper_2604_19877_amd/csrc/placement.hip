@@ -167,6 +167,18 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
           st = sa::delta_prepare(false, x.q, x.k, x.v, x.alpha_scalar, x.beta, x.state, x.state, x.out, x.slot_idx, lists[3], cnt[3], B,
                                  T, sh->H, sh->Hk, sh->dk, sh->dv, rec_scale, T, x.n_commit_rows, &gdn);
         if (st != SA_OK) return st;
+        // The partial results of the layer before are merged into ITS output at the head of this launch, next to this
+        // layer's own writes: only safe if the two outputs do not overlap.  If they do (a caller reusing one output
+        // buffer for every layer), the merge gets a launch of its own first.
+        if (!check && l > 0 && (pending.n_fa || pending.n_swa)) {
+          const size_t out_bytes = static_cast<size_t>(B) * T * sh->H * sh->dv * sizeof(float);
+          const char* const a = reinterpret_cast<const char*>(io[l - 1].out);
+          const char* const b = reinterpret_cast<const char*>(x.out);
+          if (a < b + out_bytes && b < a + out_bytes) {
+            st = sa::layer_merge_flush(&pending, stream);
+            if (st != SA_OK) return st;
+          }
+        }
         if (!check) st = sa::layer_fused_launch(fa, swa, kda, gdn, &pending, stream);
         if (st != SA_OK) return st;
         continue;

@@ -285,6 +285,40 @@ def test_random_stacks(case):
         assert (states[l][unused] == 9.0).all()
 
 
+def test_one_output_buffer_shared_by_all_layers():
+    """A caller may hand every layer the same output buffer (each layer's result is consumed before the next layer
+    writes): the merge of a layer's partial results then cannot ride on the next layer's launch, and the buffer must end
+    up holding the last layer's rows.  Contexts long enough for several page ranges per (request, KV head)."""
+    L, B, ctx, window, max_pages = 4, 4, 1500, 700, 96
+    placements = ["FSFF", "SFKF", "FFSG"]
+    pid = np.array([0, 1, 2, 0], dtype=np.int32)
+    lens = np.array([1500, 1301, 1499, 1100], dtype=np.int32)
+    layers = build_stack(5600, L, B, 1, ctx, max_pages, lens)
+    ref_outs, _ = om.placement_decode(placements, pid, layers, window, D ** -0.5, DK ** -0.5)
+    plan = sa.placement_plan_create(placements, pid)
+    shapes = sa.sa_shapes(H, H, DK, DV, HQ, HKV, D, 16)
+    ws_bytes = sa.placement_workspace_bytes(plan, shapes, 1, ctx, window)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    shared = torch.full((B, 1, H, DV), 55.0, dtype=torch.float32, device="cuda")
+    keep, ios = [], []
+    for io in layers:
+        kphys, vphys = kl.to_physical(io["kpool"], io["vpool"])
+        t = {n: dev(io[n]) for n in ("q", "k", "v", "alpha_scalar", "alpha_vec", "beta", "qa", "page_table", "seq_lens")}
+        t["state"], t["kpool"], t["vpool"] = dev(io["state"].copy()), dev(kphys), dev(vphys)
+        keep.append(t)
+        ios.append(sa.make_layer_io(q=t["q"], k=t["k"], v=t["v"], alpha_scalar=t["alpha_scalar"], alpha_vec=t["alpha_vec"],
+                                    beta=t["beta"], state=t["state"], q_attn=t["qa"], kpool=t["kpool"], vpool=t["vpool"],
+                                    n_pages=io["n_pages"], page_table=t["page_table"], seq_lens=t["seq_lens"],
+                                    max_pages=max_pages, max_seq_len=ctx, out=shared))
+    sa.placement_decode(plan, ios, shapes, 1, window, D ** -0.5, DK ** -0.5, ws, ws_bytes)
+    torch.cuda.synchronize()
+    sa.placement_plan_destroy(plan)
+    got = host(shared)
+    for r in range(B):
+        assert rel_err(got[r], ref_outs[L - 1][r]) <= OUT_TOL, r
+
+
 def test_same_placement_for_all_requests_and_empty_batch():
     """All requests on one placement: every layer is a single launch over the whole batch."""
     L, B, ctx, window, max_pages = 4, 3, 200, 64, 16
