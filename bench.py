@@ -318,9 +318,12 @@ def verify_step(np, torch, sa, gen, dev, rec, kpool, vpool, n_pages, table, max_
             sa.sa_prof_enable(False)
             ms = [t for kid in kids for t in sa.sa_prof_read(kid, reps)[2]]   # 5 tokens and more run on the chunk kernels
             avg = median(ms)
-            nbytes = alg[name + "_decode_step"]
+            one = alg[name + "_decode_step"]
+            # a pass over T tokens moves the state once and the per-token operands and outputs T times
+            nbytes = 2 * B * H * DK * DV * 4 + T * (one - 2 * B * H * DK * DV * 4)
             res["%s_T%d" % (name, T)] = {"median_us": round(avg * 1e3, 2), "tokens_per_s": round(B * T / (avg * 1e-3), 1),
-                                         "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                                         "alg_bytes": nbytes, "frac_hbm_peak": round(nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                         "frac_hbm_peak_on_one_token_bytes": round(one / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         q = dev(gen.attention_inputs(1910 + T, B, T, HQ, HKV, D, np.ones(B, dtype=np.int32), 1)["q"])
         ws_bytes = max(sa.attn_decode_workspace_bytes(B, T, HQ, HKV, D, CTX, 0),
                        sa.attn_decode_workspace_bytes(B, T, HQ, HKV, D, CTX, WINDOW))

@@ -62,7 +62,7 @@ int sa_version(void);
  *   req_idx   int32 [n_req] or NULL: the batch rows to process (NULL = rows 0..B-1, n_req ignored);
  *             rows not listed are not touched.  A row must not be listed twice.
  * Supported: (dk,dv) in {(64,64),(128,128)}, 1 <= T <= 16.  B = 0 or n_req = 0 is a no-op.
- * At (128,128) longer calls (GDN: 6 and more tokens, KDA: 7 and more) are evaluated in the chunk-parallel form (see
+ * At (128,128) calls of 7 and more tokens are evaluated in the chunk-parallel form (see
  * gdn_chunk_steps): same arguments and results, outputs and states about 1e-5 instead of 1e-6 from the fp64 recurrence.
  */
 sa_status gdn_decode_step(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
@@ -105,8 +105,8 @@ sa_status sa_state_unpack(const float* tiles, float* rowmajor, int n_tiles, int 
  * chained single steps up to rounding: every fp32 operand of a product enters as two bf16 terms (relative
  * error 2^-18), which leaves outputs and states about 1e-5 from the fp64 recurrence.  Arguments as for the
  * decode steps (n_commit included: all T outputs are produced, the state written is the one after n_commit
- * tokens); any T >= 1.  The decode steps themselves run on these kernels from 6 (GDN) and 7 (KDA) tokens per call at
- * (dk,dv) = (128,128), where they are faster (8 tokens: 53 / 60 us against 58 / 63 us at batch 64).  Gates below 2^-100 act as 2^-100 in kda_chunk_steps and below the smallest
+ * tokens); any T >= 1.  The decode steps themselves run on these kernels from 7 tokens per call at
+ * (dk,dv) = (128,128), where they are as fast or faster (8 tokens: 51 / 62 us against 54 / 62 us at batch 64).  Gates below 2^-100 act as 2^-100 in kda_chunk_steps and below the smallest
  * normal fp32 number as that number in gdn_chunk_steps.  Supported: (dk,dv) = (128,128).
  */
 sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,

@@ -118,6 +118,11 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
       sh_a[ch] = __expf(-__expf(io.A_log[h]) * softplusf(raw));
     }
   }
+  // GDN's one gate of this head, formed here with the rest of the pre-processing (the activation's long instruction
+  // sequence would otherwise sit in the middle of the update, where the tile's registers are all live)
+  float gate_scalar = 1.f;
+  if constexpr (!KDA)
+    gate_scalar = __expf(-__expf(io.A_log[h]) * softplusf(io.alpha_raw[static_cast<size_t>(b) * p.H + h] + io.dt_bias[h]));
   __syncthreads();
 
   float qsq = 0.f, ksq = 0.f;
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(D * 2) void delta_block_kernel(BlockParams p) {
       s[m].w *= a;
     }
   } else {
-    const float a = __expf(-__expf(io.A_log[h]) * softplusf(io.alpha_raw[static_cast<size_t>(b) * p.H + h] + io.dt_bias[h]));
+    const float a = gate_scalar;
 #pragma unroll
     for (int m = 0; m < RPL; ++m) {
       s[m].x *= a;

@@ -20,16 +20,20 @@
 
 namespace {
 
-template <int DK, int DV, bool KDA, bool MULTI>
-__global__ __launch_bounds__(DV * 2) void delta_step_kernel(DeltaParams p) {
-  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<DK, DV, KDA, MULTI>()];
-  delta_step_body<DK, DV, KDA, MULTI>(p, interleaved_tile(blockIdx.x, gridDim.x), blockIdx.x, park);
+// STEPS: 0 = the one-token body, else the tokens per call the multi-token body has room for.  The body for up to
+// kFewRegisterSteps tokens at 128x128 is asked to fit four wavefronts per SIMD (it does, without spilling).
+template <int DK, int DV, bool KDA, int STEPS>
+__global__ __launch_bounds__(DV * 2, (DK == 128 && STEPS == kFewRegisterSteps) ? 4 : 1) void delta_step_kernel(DeltaParams p) {
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<DK, DV, KDA, STEPS>()];
+  delta_step_body<DK, DV, KDA, STEPS>(p, interleaved_tile(blockIdx.x, gridDim.x), blockIdx.x, park);
 }
 
-// Tokens per call from which the decode steps run on the chunk-parallel kernels (measured at batch 64: GDN 5 tokens
-// 53.2 us on the register-resident kernel against 54.2 us chunked, 6 tokens 54.2 against 53.4; KDA 5 tokens 53.6 against
-// 59.7 us, 6 tokens 56.1 against 59.0, 8 tokens 62.6 against 59.8).  The register-resident kernel holds room for 6 steps.
-constexpr int kChunkedFromGdn = 6, kChunkedFromKda = 7;
+// Tokens per call from which the decode steps run on the chunk-parallel kernels, whose time hardly depends on the
+// token count up to 16 (measured at batch 64, register-resident against chunked: GDN 5 tokens 48.4 against 53 us, 6 tokens
+// 50.5 against 51.5, 7 tokens 51.5 against 51.2, 8 tokens 54 against 51.3; KDA 5 tokens 52.5 against 66 us, 6 tokens 55.8
+// against 66, 7 tokens 60 (extrapolated: its LDS room ends at 6) against 60-63, 8 tokens 62 against 61-63).  The
+// register-resident kernel holds room for 6 steps; room for 8 costs KDA a workgroup per CU (61 KiB of LDS) and 7-14 us.
+constexpr int kChunkedFromGdn = 7, kChunkedFromKda = 7;
 static_assert(kChunkedFromGdn - 1 <= kMaxRegisterSteps128 && kChunkedFromKda - 1 <= kMaxRegisterSteps128,
               "the register-resident kernel must have room for every call that is not chunked");
 
@@ -95,13 +99,15 @@ sa_status step_launch(bool dry_run, const void* q, const void* k, const void* v,
   const int kid = KDA ? SA_K_KDA : SA_K_GDN;
   const bool single = T == 1 && n_commit == 1 && !n_commit_rows;
   if (dk == 128 && single)
-    sa::launch(kid, delta_step_kernel<128, 128, KDA, false>, grid, dim3(256), 0, s, p);
+    sa::launch(kid, delta_step_kernel<128, 128, KDA, 0>, grid, dim3(256), 0, s, p);
+  else if (dk == 128 && T <= kFewRegisterSteps)
+    sa::launch(kid, delta_step_kernel<128, 128, KDA, kFewRegisterSteps>, grid, dim3(256), 0, s, p);
   else if (dk == 128)
-    sa::launch(kid, delta_step_kernel<128, 128, KDA, true>, grid, dim3(256), 0, s, p);
+    sa::launch(kid, delta_step_kernel<128, 128, KDA, kMaxRegisterSteps128>, grid, dim3(256), 0, s, p);
   else if (single)
-    sa::launch(kid, delta_step_kernel<64, 64, KDA, false>, grid, dim3(128), 0, s, p);
+    sa::launch(kid, delta_step_kernel<64, 64, KDA, 0>, grid, dim3(128), 0, s, p);
   else
-    sa::launch(kid, delta_step_kernel<64, 64, KDA, true>, grid, dim3(128), 0, s, p);
+    sa::launch(kid, delta_step_kernel<64, 64, KDA, kMaxRegisterSteps64>, grid, dim3(128), 0, s, p);
   return sa::check_launch(name);
 }
 

@@ -47,7 +47,7 @@ using sa::DeltaParams;
 
 // Steps per call for which the multi-token tile body has LDS room at 128x128 (longer calls run on the chunk-parallel
 // kernels) and at 64x64 (the entry points' limit).
-constexpr int kMaxRegisterSteps128 = 6, kMaxRegisterSteps64 = 16;
+constexpr int kMaxRegisterSteps128 = 6, kMaxRegisterSteps64 = 16, kFewRegisterSteps = 4;
 
 // The per-step scalars and value columns of a lane as they arrive from memory (bf16 still packed).
 struct StepOperands {
@@ -79,23 +79,27 @@ struct KeyVecLds {
 };
 
 // Floats of LDS one workgroup of delta_step_body needs: per wavefront and step, the parked k, q (and gate) vectors.
-template <int DK, int DV, bool KDA, bool MULTI>
+// STEPS = 0: the one-token body; otherwise the multi-token body with room for STEPS tokens per call.
+template <int DK, int DV, bool KDA, int STEPS>
 constexpr int delta_park_floats() {
-  return (DV / 32) * (!MULTI ? 1 : DK == 128 ? kMaxRegisterSteps128 : kMaxRegisterSteps64) * (KDA ? 3 : 2) * KeyVecLds<DK>::kFloats;
+  return (DV / 32) * (STEPS ? STEPS : 1) * (KDA ? 3 : 2) * KeyVecLds<DK>::kFloats;
 }
 
-// MULTI = false: exactly one committed step (T == 1, n_commit == 1), the decode hot path, with an
-// unconditional store.  MULTI = true: any T and n_commit with the tile held in registers; the
-// operands of step t+1 are requested before step t is computed.
+// STEPS = 0: exactly one committed step (T == 1, n_commit == 1), the decode hot path, with an
+// unconditional store.  STEPS > 0: any T <= STEPS and any n_commit with the tile held in registers; the
+// operands of step t+1 are requested before step t is computed.  A body built for fewer steps needs fewer
+// registers and less LDS: the one for up to kFewRegisterSteps tokens (the 4-token verify pass) runs four
+// wavefronts per SIMD like the one-token body, the one for up to kMaxRegisterSteps128 three.
 // The work of one workgroup (2*DV threads): tile `block` = (row of the request list) * H + head.  park_lds: 16-byte
-// aligned LDS of delta_park_floats<DK, DV, KDA, MULTI>() floats.
+// aligned LDS of delta_park_floats<DK, DV, KDA, STEPS>() floats.
 // EITHER (with KDA): one body for both mixers, for kernels whose workgroups run tiles of either kind: a tile with
 // scalar_gate set is a GDN tile, whose one gate is written to all key rows of the parked gate vector; everything after
 // the fetch is the same code, so such a kernel carries one tile body (and its registers) instead of two.
-template <int DK, int DV, bool KDA, bool MULTI, bool EITHER = false>
+template <int DK, int DV, bool KDA, int STEPS, bool EITHER = false>
 __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int block, const int start, float* const park_lds,
                                                 const bool scalar_gate = false) {
   static_assert(!EITHER || KDA, "the body for either mixer is the per-channel one");
+  constexpr bool MULTI = STEPS > 0;
   constexpr int RPL = DK / 8;  // rows per lane
   using Park = KeyVecLds<DK>;
   // Register m of a lane holds row (m + rot) mod RPL of the lane's rows: workgroups launched next to each other start
@@ -124,8 +128,29 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
       !MULTI ? 1 : __builtin_amdgcn_readfirstlane(p.n_commit_rows ? min(max(p.n_commit_rows[b], 0), T) : p.n_commit);
 
   const size_t tile = (static_cast<size_t>(slot) * p.H + h) * (DK * DV);
-  const float* sin = p.state_in + tile + static_cast<size_t>(row0) * DV + col0;
-  float* sout = p.state_out + tile + static_cast<size_t>(row0) * DV + col0;
+  // Where register m's row of this lane sits.  The multi-token body addresses the tile as a base that is the same for
+  // the whole workgroup (scalar registers) plus one 32-bit lane offset, and forms the store offsets again where the
+  // stores are (the offset passes through an empty asm statement there), so that no address is held across the steps:
+  // 64-bit addresses of 16 rows, twice, are what kept it from four wavefronts per SIMD.  The one-token body has the
+  // registers and runs 3 % faster with plain per-row pointers (44.1 against 45.6 us at batch 64).
+  const float* const tile_in = p.state_in + tile;
+  float* const tile_out = p.state_out + tile;
+  const uint32_t lane_bytes = static_cast<uint32_t>(row0 * DV + col0) * 4u;
+  const auto row_bytes = [rot](int m) { return static_cast<uint32_t>(((m + rot) & (RPL - 1)) * DV) * 4u; };
+  const float* const lane_in = tile_in + static_cast<size_t>(row0) * DV + col0;
+  float* const lane_out = tile_out + static_cast<size_t>(row0) * DV + col0;
+  const auto in_at = [=](uint32_t lane_off, int m) {
+    if constexpr (MULTI)
+      return reinterpret_cast<const float*>(reinterpret_cast<const char*>(tile_in) + (lane_off + row_bytes(m)));
+    else
+      return lane_in + ((m + rot) & (RPL - 1)) * DV;
+  };
+  const auto out_at = [=](uint32_t lane_off, int m) {
+    if constexpr (MULTI)
+      return reinterpret_cast<float*>(reinterpret_cast<char*>(tile_out) + (lane_off + row_bytes(m)));
+    else
+      return lane_out + ((m + rot) & (RPL - 1)) * DV;
+  };
 
   // All requests first: the small operands of step 0, then the RPL state rows of this lane.  The
   // scheduling barrier keeps the compiler from sinking any of them towards its first use, which
@@ -136,9 +161,9 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   // step), and parks them as fp32 in a region of LDS of its own; a step then reads its lane's rows from there.
   // Per-lane global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row): as many
   // load instructions per 4 steps as the state tile itself takes.  No other wavefront reads the region: no barrier.
-  constexpr int kSteps = !MULTI ? 1 : DK == 128 ? kMaxRegisterSteps128 : kMaxRegisterSteps64;
+  constexpr int kSteps = MULTI ? STEPS : 1;
   constexpr int kVecs = KDA ? 3 : 2;  // k, q, gates
-  static_assert(delta_park_floats<DK, DV, KDA, MULTI>() == (DV / 32) * kSteps * kVecs * Park::kFloats);
+  static_assert(delta_park_floats<DK, DV, KDA, STEPS>() == (DV / 32) * kSteps * kVecs * Park::kFloats);
   float* const my_park = park_lds + wave * (kSteps * kVecs * Park::kFloats);
   float2 gate_fetch[KDA ? kSteps : 1];
   uint32_t k_fetch[kSteps], q_fetch[kSteps];
@@ -176,7 +201,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   }
   float4 s[RPL];
 #pragma unroll
-  for (int m = 0; m < RPL; ++m) s[m] = load_state(sin + ((m + rot) & (RPL - 1)) * DV);
+  for (int m = 0; m < RPL; ++m) s[m] = load_state(in_at(lane_bytes, m));
   __builtin_amdgcn_sched_barrier(0);
   {
     // where this lane's fetched values go: DK = 128: rows 2*lane, 2*lane+1 of k, of q and of the gates; DK = 64: rows
@@ -209,7 +234,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
 
   if (MULTI && n_commit == 0 && p.state_out != p.state_in) {
 #pragma unroll
-    for (int m = 0; m < RPL; ++m) store_state(sout + ((m + rot) & (RPL - 1)) * DV, s[m]);
+    for (int m = 0; m < RPL; ++m) store_state(out_at(lane_bytes, m), s[m]);
   }
 
   for (int t = 0; t < T; ++t) {
@@ -220,14 +245,6 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
     }
     // this lane's rows of k, q (and the gates) of step t, in register order
     const float* const mine = my_park + t * (kVecs * Park::kFloats) + r8 * Park::kGroupStride;
-    float kf[RPL], qf[RPL];
-#pragma unroll
-    for (int j = 0; j < RPL / 4; ++j) {
-      const float4 kk = *reinterpret_cast<const float4*>(mine + 4 * j);
-      const float4 qq = *reinterpret_cast<const float4*>(mine + Park::kFloats + 4 * j);
-      kf[4 * j] = kk.x, kf[4 * j + 1] = kk.y, kf[4 * j + 2] = kk.z, kf[4 * j + 3] = kk.w;
-      qf[4 * j] = qq.x, qf[4 * j + 1] = qq.y, qf[4 * j + 2] = qq.z, qf[4 * j + 3] = qq.w;
-    }
     const float beta = cur.beta;
 
     if constexpr (KDA) {
@@ -271,19 +288,47 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
       }
     }
 
+    // The one-token body reads this lane's k and q from LDS up front (the reads land while the tile's loads are still in
+    // flight) and keeps them: it has the registers.  The multi-token body reads them four rows at a time where they
+    // are used, and k once more for the update below: held for a whole step they cost 32 registers next to the tile's
+    // 64, and with them the body does not fit four wavefronts per SIMD.
     float4 u = {0.f, 0.f, 0.f, 0.f}, w = {0.f, 0.f, 0.f, 0.f};
     float kq = 0.f;
+    float k_kept[MULTI ? 1 : RPL], q_kept[MULTI ? 1 : RPL];
+    if constexpr (!MULTI) {
 #pragma unroll
-    for (int m = 0; m < RPL; ++m) {
-      u.x = fmaf(s[m].x, kf[m], u.x);
-      u.y = fmaf(s[m].y, kf[m], u.y);
-      u.z = fmaf(s[m].z, kf[m], u.z);
-      u.w = fmaf(s[m].w, kf[m], u.w);
-      w.x = fmaf(s[m].x, qf[m], w.x);
-      w.y = fmaf(s[m].y, qf[m], w.y);
-      w.z = fmaf(s[m].z, qf[m], w.z);
-      w.w = fmaf(s[m].w, qf[m], w.w);
-      kq = fmaf(kf[m], qf[m], kq);
+      for (int j = 0; j < RPL / 4; ++j) {
+        const float4 kk = *reinterpret_cast<const float4*>(mine + 4 * j);
+        const float4 qq = *reinterpret_cast<const float4*>(mine + Park::kFloats + 4 * j);
+        k_kept[4 * j] = kk.x, k_kept[4 * j + 1] = kk.y, k_kept[4 * j + 2] = kk.z, k_kept[4 * j + 3] = kk.w;
+        q_kept[4 * j] = qq.x, q_kept[4 * j + 1] = qq.y, q_kept[4 * j + 2] = qq.z, q_kept[4 * j + 3] = qq.w;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < RPL / 4; ++j) {
+      float kf[4], qf[4];
+      if constexpr (MULTI) {
+        const float4 kk = *reinterpret_cast<const float4*>(mine + 4 * j);
+        const float4 qq = *reinterpret_cast<const float4*>(mine + Park::kFloats + 4 * j);
+        kf[0] = kk.x, kf[1] = kk.y, kf[2] = kk.z, kf[3] = kk.w;
+        qf[0] = qq.x, qf[1] = qq.y, qf[2] = qq.z, qf[3] = qq.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) kf[e] = k_kept[4 * j + e], qf[e] = q_kept[4 * j + e];
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float4& x = s[4 * j + e];
+        u.x = fmaf(x.x, kf[e], u.x);
+        u.y = fmaf(x.y, kf[e], u.y);
+        u.z = fmaf(x.z, kf[e], u.z);
+        u.w = fmaf(x.w, kf[e], u.w);
+        w.x = fmaf(x.x, qf[e], w.x);
+        w.y = fmaf(x.y, qf[e], w.y);
+        w.z = fmaf(x.z, qf[e], w.z);
+        w.w = fmaf(x.w, qf[e], w.w);
+        kq = fmaf(kf[e], qf[e], kq);
+      }
     }
     u.x = reduce_r8(u.x);
     u.y = reduce_r8(u.y);
@@ -320,15 +365,32 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
         ds.z *= r;
         ds.w *= r;
       }
+      // k again, through an offset the compiler cannot see through (it would otherwise keep the first read's registers)
+      int again = 0;
+      if constexpr (MULTI) asm volatile("" : "+v"(again));
 #pragma unroll
-      for (int m = 0; m < RPL; ++m) {
-        s[m].x = fmaf(kf[m], ds.x, s[m].x);
-        s[m].y = fmaf(kf[m], ds.y, s[m].y);
-        s[m].z = fmaf(kf[m], ds.z, s[m].z);
-        s[m].w = fmaf(kf[m], ds.w, s[m].w);
+      for (int j = 0; j < RPL / 4; ++j) {
+        float kf[4];
+        if constexpr (MULTI) {
+          const float4 kk = *reinterpret_cast<const float4*>(mine + again + 4 * j);
+          kf[0] = kk.x, kf[1] = kk.y, kf[2] = kk.z, kf[3] = kk.w;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) kf[e] = k_kept[4 * j + e];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float4& x = s[4 * j + e];
+          x.x = fmaf(kf[e], ds.x, x.x);
+          x.y = fmaf(kf[e], ds.y, x.y);
+          x.z = fmaf(kf[e], ds.z, x.z);
+          x.w = fmaf(kf[e], ds.w, x.w);
+        }
       }
     }
     if (!MULTI || t + 1 == n_commit) {
+      uint32_t here = lane_bytes;
+      if constexpr (MULTI) asm volatile("" : "+v"(here));
 #pragma unroll
       for (int m = 0; m < RPL; ++m) {
         float4 x = s[m];
@@ -338,7 +400,7 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
           x.z *= carry;
           x.w *= carry;
         }
-        store_state(sout + ((m + rot) & (RPL - 1)) * DV, x);
+        store_state(out_at(here, m), x);
       }
     }
     if (r8 == 0) {

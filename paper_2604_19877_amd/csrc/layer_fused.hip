@@ -42,12 +42,12 @@ template <bool MULTI>
 __device__ __forceinline__ void run_tile(const sa::DeltaParams& kda, const sa::DeltaParams& gdn, int tile, int n_kda, float* park) {
   const bool is_gdn = tile >= n_kda;
   if constexpr (!MULTI) {
-    delta_step_body<128, 128, true, false, true>(is_gdn ? gdn : kda, is_gdn ? tile - n_kda : tile, blockIdx.x, park, is_gdn);
+    delta_step_body<128, 128, true, 0, true>(is_gdn ? gdn : kda, is_gdn ? tile - n_kda : tile, blockIdx.x, park, is_gdn);
   } else {
     if (is_gdn)
-      delta_step_body<128, 128, false, true>(gdn, tile - n_kda, blockIdx.x, park);
+      delta_step_body<128, 128, false, kFewRegisterSteps>(gdn, tile - n_kda, blockIdx.x, park);
     else
-      delta_step_body<128, 128, true, true>(kda, tile, blockIdx.x, park);
+      delta_step_body<128, 128, true, kFewRegisterSteps>(kda, tile, blockIdx.x, park);
   }
 }
 
@@ -66,7 +66,7 @@ template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
   __shared__ AttnShared sm;
   // one region for whichever tile body this workgroup runs (the KDA body needs the larger one)
-  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI>()];
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI ? kFewRegisterSteps : 0>()];
   const int id = blockIdx.x;
   if (id < p.end_prev) {
     merge_items(p.prev, 2 * id);
@@ -95,7 +95,7 @@ struct RecurrentLayerParams {
 
 template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
-  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI>()];
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI ? kFewRegisterSteps : 0>()];
   if (static_cast<int>(blockIdx.x) < p.end_prev) {
     merge_items(p.prev, 2 * blockIdx.x);
     return;
@@ -162,7 +162,7 @@ sa_status sa::layer_fused_launch(const sa::AttnLaunch& fa, const sa::AttnLaunch&
     p.end_fa = static_cast<int>(n_prev + n_fa);
     p.end_swa = static_cast<int>(n_prev + n_fa + n_swa);
     p.end_kda = static_cast<int>(n_prev + n_fa + n_swa + n_kda);
-    // The multi-token tile body parks k, q and gate vectors of up to 6 steps in LDS (45 KiB): with the attention body's
+    // The multi-token tile body parks k, q and gate vectors of up to 4 steps in LDS (30 KiB): with the attention body's
     // 32.5 KiB that already limits a CU to the 2 workgroups the K/V stream wants, so no padding is requested.
     if (multi)
       sa::launch(SA_K_LAYER, layer_decode_kernel<true>, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, p);
