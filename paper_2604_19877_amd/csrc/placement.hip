@@ -17,7 +17,9 @@ struct sa_plan {
   int L = 0, B = 0;
   // counts[l][m] requests run mixer m at layer l; their ids sit at offset[l][m] of the device list.
   std::vector<int> counts, offsets;
-  int32_t* dev_lists = nullptr;  // L*B ints: per layer the requests grouped by mixer (F,S,K,G)
+  int32_t* dev_lists = nullptr;  // 2*L*B ints.  First L*B: per layer the requests grouped by mixer (F,S,K,G).  Then L*B: per
+                                 // layer the requests of both recurrent mixers as ONE list in request order, a GDN request with
+                                 // its sign bit set (~r): the order the fused one-token launch visits the state tiles in.
 };
 
 namespace {
@@ -58,7 +60,7 @@ extern "C" sa_status placement_plan_create(const char* const* placements, int n_
   plan->B = B;
   plan->counts.assign(static_cast<size_t>(L) * 4, 0);
   plan->offsets.assign(static_cast<size_t>(L) * 4, 0);
-  std::vector<int32_t> lists(static_cast<size_t>(L) * B);
+  std::vector<int32_t> lists(2 * static_cast<size_t>(L) * B);
   for (int l = 0; l < L; ++l) {
     int at = 0;
     for (int m = 0; m < 4; ++m) {
@@ -66,6 +68,13 @@ extern "C" sa_status placement_plan_create(const char* const* placements, int n_
       for (int r = 0; r < B; ++r)
         if (mixer_index(placements[placement_id[r]][l]) == m) lists[static_cast<size_t>(l) * B + at++] = r;
       plan->counts[l * 4 + m] = l * B + at - plan->offsets[l * 4 + m];
+    }
+    int32_t* merged = lists.data() + (static_cast<size_t>(L) + l) * B;
+    int n = 0;
+    for (int r = 0; r < B; ++r) {
+      const int m = mixer_index(placements[placement_id[r]][l]);
+      if (m == 2) merged[n++] = r;
+      if (m == 3) merged[n++] = ~r;
     }
   }
   if (!lists.empty()) {
@@ -179,7 +188,8 @@ extern "C" sa_status placement_decode(const sa_plan* plan, const sa_layer_io* io
             if (st != SA_OK) return st;
           }
         }
-        if (!check) st = sa::layer_fused_launch(fa, swa, kda, gdn, &pending, stream);
+        if (!check)
+          st = sa::layer_fused_launch(fa, swa, kda, gdn, plan->dev_lists + (static_cast<size_t>(plan->L) + l) * B, &pending, stream);
         if (st != SA_OK) return st;
         continue;
       }
