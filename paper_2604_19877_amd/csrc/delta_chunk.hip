@@ -30,8 +30,9 @@
 // The workgroup stages each chunk's K and Q in LDS once (token-major for the A operands of
 // K S_0 / Q S_0 and the Gram matrices, channel-major for the A operand of K^T Delta), double
 // buffered with one barrier per chunk.  Each wavefront solves the triangular system for its own
-// columns in four 4-row stages: rows live 4 to a lane, so a stage is a 4x4 solve inside the lanes
-// of one group, a broadcast of its 4 results, and a 4x4 block update in the later groups.
+// columns by 4-row groups: rows live 4 to a lane, so the 4x4 diagonal blocks are eliminated inside
+// the lanes (once, for all groups together), and three stages of "broadcast a group's 4 results,
+// 4x4 block update in the later groups" finish it.
 #include "common.h"
 #include "delta_device.h"
 
@@ -72,7 +73,7 @@ constexpr int kChnB = kD * kChRowB + (kD / 8) * kChGroupPadB;   // bytes of one 
 __device__ __forceinline__ int chn_row(int channel) { return channel * kChRowB + (channel >> 3) * kChGroupPadB; }
 constexpr int kStageB = 2 * kC * kTokRowB + kChnB;  // one chunk's K, Q and transposed K
 constexpr int kMatRow = 20;      // floats per row of the per-wavefront 16x16 matrices (16 + 4)
-constexpr int kWaveB = (2 * kC * kMatRow + kC * 4 + 64) * 4;  // A (off-diagonal blocks), M, diagonal blocks of A, dump slots
+constexpr int kWaveB = (2 * kC * kMatRow + kC * 4) * 4;  // L', M, diagonal blocks of A
 
 // Two-term split with round-to-nearest in both terms: x = hi + lo up to 2^-18 |x|.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -100,6 +101,11 @@ __device__ __forceinline__ bf16x8 join8(const u32x2& a, const u32x2& b) {
 __device__ __forceinline__ f32x4 mfma_two_terms(const u32x2& a, const Split4x2& b, const f32x4& acc) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(join8(a, a), join8(b.hi, b.lo), acc, 0, 0, 0);
 }
+constexpr int kChRowTile = 16 * kChRowB + 2 * kChGroupPadB;  // bytes from channel c's row to channel c+16's
+
+// 2^x by the bare instruction: results below the smallest normal number come out as 0, which is what the decay
+// factors here may do (the library call spends five more instructions on keeping them).
+__device__ __forceinline__ float pow2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // x of the lane D places down the same row of 16 lanes, 0 for the first D lanes of a row.
 template <int D>
@@ -107,26 +113,51 @@ __device__ __forceinline__ float row_shr(float x) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x110 + D, 0xf, 0xf, true));
 }
 
-// Forward substitution (I + A) delta = rhs for this wavefront's 2 x 16 columns, rows 4 to a lane.
-// a_off holds A with the 4x4 diagonal blocks zeroed ([16][kMatRow]), a_dia those blocks ([16][4]).
-// Stage gp: the lanes of row group gp finish their 4 rows (the other groups run the same code with zero
-// coefficients), broadcast them, and the later groups subtract their block's share.
-__device__ __forceinline__ void solve_rows(f32x4 (&rhs)[2], const float* a_off, const float* a_dia, int n, int g) {
-  const f32x4 dia1 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 1) * 4);
-  const f32x4 dia2 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 2) * 4);
-  const f32x4 dia3 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 3) * 4);
+// The triangular system (I + A) delta = rhs, A = D + L with D the four 4x4 diagonal blocks (a lane holds 4 rows, so a
+// block stays inside the lanes of one row group) and L the blocks below them.  Both sides are multiplied by (I + D)^-1
+// first: every row group does that 4-row substitution once, at the same time, on its right-hand sides, and the lanes
+// that formed L apply it to the column of L they hold.  What remains, (I + L') delta = rhs' with L' = (I + D)^-1 L, is
+// solved block row by block row with nothing but broadcasts and 4x4 block updates.
+struct DiagBlock {
+  f32x4 r1, r2, r3;  // rows 1..3 of this lane's row group's block of D (strictly lower: columns 0..2 are used)
+};
+__device__ __forceinline__ void diag_solve(f32x4& x, const DiagBlock& d) {
+  x[1] = fmaf(-d.r1[0], x[0], x[1]);
+  x[2] = fmaf(-d.r2[1], x[1], fmaf(-d.r2[0], x[0], x[2]));
+  x[3] = fmaf(-d.r3[2], x[2], fmaf(-d.r3[1], x[1], fmaf(-d.r3[0], x[0], x[3])));
+}
+
+// Lane (n, g) brings a[j] = A[4g+j][n] (0 for n >= 4g+j) and m[j] = M[4g+j][n] (0 for n > 4g+j).  Leaves M in m_low
+// ([16][kMatRow]), L' in a_off ([16][kMatRow], zero on and above the diagonal blocks) and returns the lane's block of D,
+// which went through a_dia ([16][4]).
+__device__ __forceinline__ DiagBlock publish_system(const f32x4& a, const f32x4& m, float* a_off, float* m_low, float* a_dia, int n, int g) {
+  if ((n >> 2) == g) {
 #pragma unroll
-  for (int gp = 0; gp < 4; ++gp) {
-    const bool now = g == gp;
-    const float c10 = now ? dia1[0] : 0.f, c20 = now ? dia2[0] : 0.f, c21 = now ? dia2[1] : 0.f;
-    const float c30 = now ? dia3[0] : 0.f, c31 = now ? dia3[1] : 0.f, c32 = now ? dia3[2] : 0.f;
+    for (int j = 0; j < 4; ++j) a_dia[(4 * g + j) * 4 + (n & 3)] = a[j];
+  }
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      rhs[c][1] = fmaf(-c10, rhs[c][0], rhs[c][1]);
-      rhs[c][2] = fmaf(-c21, rhs[c][1], fmaf(-c20, rhs[c][0], rhs[c][2]));
-      rhs[c][3] = fmaf(-c32, rhs[c][2], fmaf(-c31, rhs[c][1], fmaf(-c30, rhs[c][0], rhs[c][3])));
-    }
-    if (gp == 3) break;  // nothing follows the last group
+  for (int j = 0; j < 4; ++j) m_low[(4 * g + j) * kMatRow + n] = m[j];
+  wave_lds_sync();
+  DiagBlock d;
+  d.r1 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 1) * 4);
+  d.r2 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 2) * 4);
+  d.r3 = *reinterpret_cast<const f32x4*>(a_dia + (4 * g + 3) * 4);
+  const bool below = (n >> 2) < g;
+  f32x4 l = {below ? a[0] : 0.f, below ? a[1] : 0.f, below ? a[2] : 0.f, below ? a[3] : 0.f};
+  diag_solve(l, d);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) a_off[(4 * g + j) * kMatRow + n] = l[j];
+  wave_lds_sync();
+  return d;
+}
+
+// rhs turns into delta in place, for this wavefront's 2 x 16 columns.  Stage gp: the rows of group gp are final; they
+// are broadcast and the later groups subtract their block's share (the other groups run the same code on zeros).
+__device__ __forceinline__ void solve_rows(f32x4 (&rhs)[2], const float* a_off, const DiagBlock& dia, int n, int g) {
+  diag_solve(rhs[0], dia);
+  diag_solve(rhs[1], dia);
+#pragma unroll
+  for (int gp = 0; gp < 3; ++gp) {
     float d[2][4];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
@@ -169,12 +200,18 @@ __device__ __forceinline__ void store_tile(const f32x4 (&S)[8][2], float* sout, 
     }
 }
 
+// A value that is the same in every lane, moved to a scalar register.  The empty asm hides where it came from:
+// the compiler drops a bare readfirstlane of a value it can prove uniform and then leaves that value in vector registers.
+__device__ __forceinline__ int to_scalar(int x) {
+  asm volatile("" : "+v"(x));
+  return __builtin_amdgcn_readfirstlane(x);
+}
+
 // Offsets are formed in bytes in 32 bits so that a load is "scalar base + vector offset".
 template <typename V>
 __device__ __forceinline__ V load_at(const void* base, uint32_t byte_off) {
   return *reinterpret_cast<const V*>(static_cast<const unsigned char*>(base) + byte_off);
 }
-
 // What a thread fetches from global memory for one chunk.
 struct ChunkFetch {
   u32x4 kst, qst;     // staging: 8 channels of one token of K and of Q
@@ -199,41 +236,66 @@ __device__ __forceinline__ ChunkOffsets chunk_offsets(const ChunkParams& p, int 
   return o;
 }
 
-// All addresses are a per-chunk scalar base plus a 32-bit lane offset (a chunk spans < 4 GiB).  `full` holds the
-// offsets of a chunk that lies wholly inside the call (computed once per kernel).  The call's last chunk may be
-// ragged: tokens past the end are read from the last valid token and then replaced by values that leave the
-// state alone: k = q = v = 0, alpha = 1, beta = 0.
-__device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p, const ChunkOffsets& full, size_t row0, int t0, int h,
-                                            int hk, int col, int g, int n) {
-  const int lim = p.T - 1 - t0;  // last valid token of the chunk
-  const size_t kq_base = ((row0 + t0) * p.Hk + hk) * kD;
-  const size_t base = (row0 + t0) * p.H + h;
-  if (lim >= kC - 1) {
-    f.kst = load_at<u32x4>(p.k + kq_base, full.kq);
-    f.qst = load_at<u32x4>(p.q + kq_base, full.kq);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) f.v[j] = load_at<uint32_t>(p.v + base * kD, full.v[j]);
-    f.alpha = load_at<float>(p.alpha + base, full.gate);
-    f.beta = load_at<float>(p.beta + base, full.gate);
-    return;
+// All addresses are a per-chunk scalar base plus a 32-bit lane offset (a chunk spans < 4 GiB).  The bases advance
+// from chunk to chunk by fixed strides.  `offs` holds the offsets of a chunk that lies wholly inside the call, computed
+// once per kernel; only the call's last chunk can be ragged, and it overwrites them: tokens past the end are read from
+// the last valid token and then replaced by values that leave the state alone: k = q = v = 0, alpha = 1, beta = 0.
+// The offsets pass through an empty asm in the block that loads: a load takes the form "scalar base + 32-bit lane
+// offset" only when the widening of the offset sits next to it; otherwise the compiler widens the chunk-invariant
+// offsets once, keeps them as 64-bit pairs for the whole kernel and adds the chunk's base to each with the vector unit.
+struct ChunkBases {
+  const uint16_t *k, *q, *v;
+  const float *alpha, *beta;
+};
+__device__ __forceinline__ ChunkBases chunk_bases(const ChunkParams& p, size_t row0, int h, int hk) {
+  const size_t kq = (row0 * p.Hk + hk) * kD, base = row0 * p.H + h;
+  return ChunkBases{p.k + kq, p.q + kq, p.v + base * kD, p.alpha + base, p.beta + base};
+}
+__device__ __forceinline__ void next_chunk(ChunkBases& at, const ChunkParams& p) {
+  at.k += kC * p.Hk * kD;
+  at.q += kC * p.Hk * kD;
+  at.v += kC * p.H * kD;
+  at.alpha += kC * p.H;
+  at.beta += kC * p.H;
+}
+__device__ __forceinline__ void opaque(ChunkOffsets& o) {
+  asm volatile("" : "+v"(o.kq), "+v"(o.v[0]), "+v"(o.v[1]), "+v"(o.v[2]), "+v"(o.v[3]), "+v"(o.gate));
+}
+// A chunk is fetched in two parts, each straight into the registers the previous chunk's values have just left: K and
+// Q for staging as soon as the previous chunk is staged (this part also switches `offs` over for a ragged chunk), the
+// per-lane values once the previous chunk's right-hand sides are formed.  `lim` is the chunk's last valid token.
+__device__ __forceinline__ void fetch_staging(ChunkFetch& f, const ChunkParams& p, const ChunkBases& at, ChunkOffsets& offs, int lim,
+                                              int col, int g, int n) {
+  const bool ragged = lim < kC - 1;
+  if (ragged) {
+    // The empty asm, which the offsets below depend on, keeps this a branch: as selects, their multiplications would run in every chunk.
+    asm volatile("" : "+s"(lim));
+    offs = chunk_offsets(p, lim, col, g, n);
   }
-  const ChunkOffsets o = chunk_offsets(p, lim, col, g, n);
-  const int tok = static_cast<int>(threadIdx.x) >> 4;
-  const u32x4 kk = load_at<u32x4>(p.k + kq_base, o.kq), qq = load_at<u32x4>(p.q + kq_base, o.kq);
-  const bool live = tok <= lim;
+  asm volatile("" : "+v"(offs.kq));
+  f.kst = load_at<u32x4>(at.k, offs.kq);
+  f.qst = load_at<u32x4>(at.q, offs.kq);
+  if (!ragged) return;
+  asm volatile("");
+  const bool live = (static_cast<int>(threadIdx.x) >> 4) <= lim;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    f.kst[e] = live ? kk[e] : 0u;
-    f.qst[e] = live ? qq[e] : 0u;
+    f.kst[e] = live ? f.kst[e] : 0u;
+    f.qst[e] = live ? f.qst[e] : 0u;
   }
+}
+__device__ __forceinline__ void fetch_lane(ChunkFetch& f, const ChunkBases& at, ChunkOffsets& offs, int lim, int g, int n) {
+  asm volatile("" : "+v"(offs.v[0]), "+v"(offs.v[1]), "+v"(offs.v[2]), "+v"(offs.v[3]), "+v"(offs.gate));
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t x = load_at<uint32_t>(p.v + base * kD, o.v[j]);
-    f.v[j] = 4 * g + j <= lim ? x : 0u;
-  }
-  const float a = load_at<float>(p.alpha + base, o.gate), bt = load_at<float>(p.beta + base, o.gate);
-  f.alpha = n <= lim ? a : 1.f;
-  f.beta = n <= lim ? bt : 0.f;
+  for (int j = 0; j < 4; ++j) f.v[j] = load_at<uint32_t>(at.v, offs.v[j]);
+  f.alpha = load_at<float>(at.alpha, offs.gate);
+  f.beta = load_at<float>(at.beta, offs.gate);
+  if (lim >= kC - 1) return;
+  asm volatile("");  // a branch, not selects
+#pragma unroll
+  for (int j = 0; j < 4; ++j) f.v[j] = 4 * g + j <= lim ? f.v[j] : 0u;
+  f.alpha = n <= lim ? f.alpha : 1.f;
+  f.beta = n <= lim ? f.beta : 0.f;
 }
 
 // ONE: the call is a single chunk (T <= 16, a verify pass): nothing is prefetched for a next chunk and one staging
@@ -242,13 +304,15 @@ __device__ __forceinline__ void fetch_chunk(ChunkFetch& f, const ChunkParams& p,
 template <bool ONE>
 __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int r = blockIdx.x / p.H;
+  // Every index here is the same for the whole workgroup; saying so keeps every base address in scalar registers
+  // (the divisions run on the vector unit and their results stay in vector registers, and everything computed
+  // from them with them, unless they are moved across by hand).
+  const int r = to_scalar(blockIdx.x / p.H);
   const int h = blockIdx.x - r * p.H;
-  // Both indices are the same for the whole workgroup; saying so keeps every base address in scalar registers.
   const int b = __builtin_amdgcn_readfirstlane(p.req_idx ? p.req_idx[r] : r);
   const int slot = __builtin_amdgcn_readfirstlane(p.slot_idx ? p.slot_idx[b] : b);
   const int n_commit = __builtin_amdgcn_readfirstlane(p.n_commit_rows ? min(max(p.n_commit_rows[b], 0), p.T) : p.n_commit);
-  const int hk = h / (p.H / p.Hk);
+  const int hk = to_scalar(h / (p.H / p.Hk));
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int n = lane & 15, g = lane >> 4;
@@ -256,9 +320,9 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
   const size_t row0 = static_cast<size_t>(b) * p.T;
 
   float* const wave_mat = reinterpret_cast<float*>(lds + (ONE ? 1 : 2) * kStageB + wave * kWaveB);
-  float* const a_off = wave_mat;                      // [16][kMatRow]: beta_t g(t,i) k_t.k_i for i in an earlier 4-row group
+  float* const a_off = wave_mat;                      // [16][kMatRow]: A = beta_t g(t,i) k_t.k_i below its diagonal blocks, block-diagonal part eliminated
   float* const m_low = wave_mat + kC * kMatRow;       // [16][kMatRow]: g(t,i) q_t.k_i for i <= t
-  float* const a_dia = wave_mat + 2 * kC * kMatRow;   // [16][4]: the same products for i in t's own group, i < t
+  float* const a_dia = wave_mat + 2 * kC * kMatRow;   // [16][4]: A for i in t's own group, i < t
 
   // Uniform tile base plus a 32-bit lane offset, so that addresses cost one register each.
   const size_t tile = (static_cast<size_t>(slot) * p.H + h) * (kD * kD);
@@ -267,10 +331,15 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
   const uint32_t lane_off = static_cast<uint32_t>(4 * g * kD + col);
 
   // Kept in registers for the whole call (the empty asm stops the compiler from recomputing them per chunk).
-  ChunkOffsets full = chunk_offsets(p, kC - 1, col, g, n);
-  asm volatile("" : "+v"(full.kq), "+v"(full.v[0]), "+v"(full.v[1]), "+v"(full.v[2]), "+v"(full.v[3]), "+v"(full.gate));
-  ChunkFetch cur, nxt;
-  fetch_chunk(cur, p, full, row0, 0, h, hk, col, g, n);
+  ChunkOffsets offs = chunk_offsets(p, kC - 1, col, g, n);
+  opaque(offs);
+  ChunkBases at = chunk_bases(p, row0, h, hk);
+  float* out_at = p.out + (row0 * p.H + h) * kD;   // the current chunk's first output row, this head
+  uint32_t out_off = (static_cast<uint32_t>(4 * g * p.H * kD + col)) * 4u;  // bytes from there to token 4g, this lane's columns
+  asm volatile("" : "+v"(out_off));
+  ChunkFetch cur;
+  fetch_staging(cur, p, at, offs, p.T - 1, col, g, n);
+  fetch_lane(cur, at, offs, p.T - 1, g, n);
   // S[rt][c][j]: key row 16 rt + 4 g + j, value column col + c.
   f32x4 S[8][2];
 #pragma unroll
@@ -309,11 +378,12 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
     __syncthreads();
     // The buffer written above was last read two chunks ago, and every wavefront has passed the
     // previous chunk's barrier since, so one barrier per chunk is enough.
-    if (!ONE && ch + 1 < n_chunks) {
-      // An opaque copy of the next chunk's first token keeps the address arithmetic here, in scalar registers.
-      int t_next = t0 + kC;
-      asm volatile("" : "+s"(t_next));
-      fetch_chunk(nxt, p, full, row0, t_next, h, hk, col, g, n);
+    const bool more = !ONE && ch + 1 < n_chunks;
+    const int lim = p.T - 1 - t0, lim_next = lim - kC;  // last valid token of this chunk and of the next
+    const bool whole = lim >= kC - 1;
+    if (more) {
+      next_chunk(at, p);
+      fetch_staging(cur, p, at, offs, lim_next, col, g, n);
     }
 
     // K S_0 and Q S_0 for this wavefront's 32 columns (rows = tokens 4g+j), and the Gram matrices
@@ -343,7 +413,7 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
     // product of gates can overflow or divide by an underflowed one.  Every lane holds alpha and beta of
     // token lane%16; a gate below the smallest normal number acts as that number.
     // Inclusive prefix sum L_n over the 16 lanes of a row with row shifts (a lane without a source adds 0).
-    float log_sum = log2f(fmaxf(cur.alpha, 1.17549435e-38f));
+    float log_sum = __builtin_amdgcn_logf(fmaxf(cur.alpha, 1.17549435e-38f));  // the bare instruction: its operand is a normal number
     log_sum += row_shr<1>(log_sum);
     log_sum += row_shr<2>(log_sum);
     log_sum += row_shr<4>(log_sum);
@@ -358,21 +428,19 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float lt = __shfl(log_sum, 4 * g + j);
-      g_start[j] = exp2f(lt + c_log);       // g(t,-1) times the common factor: applies to products with the registers' state
-      g_end[j] = exp2f(end_base - lt);      // g(15,t) over the factor the registers carry after this chunk
-      ratio[j] = exp2f(fminf(lt - log_sum, 0.f));  // g(t,n) for t = 4g+j >= n (unused otherwise)
+      g_start[j] = pow2(lt + c_log);      // g(t,-1) times the common factor: applies to products with the registers' state
+      g_end[j] = pow2(end_base - lt);     // g(15,t) over the factor the registers carry after this chunk
+      ratio[j] = pow2(fminf(lt - log_sum, 0.f));  // g(t,n) for t = 4g+j >= n (unused otherwise)
       beta_t[j] = __shfl(cur.beta, 4 * g + j);
     }
-    const bool own_group = (n >> 2) == g;
+    f32x4 a_col, m_col;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int t = 4 * g + j;
-      const float a = n < t ? beta_t[j] * ratio[j] * kk[j] : 0.f;
-      a_off[t * kMatRow + n] = (n >> 2) < g ? a : 0.f;
-      a_dia[own_group ? t * 4 + (n & 3) : kC * 4 + lane] = a;  // other lanes write to a dump slot of their own
-      m_low[t * kMatRow + n] = n <= t ? ratio[j] * qk[j] : 0.f;
+      a_col[j] = n < t ? beta_t[j] * ratio[j] * kk[j] : 0.f;
+      m_col[j] = n <= t ? ratio[j] * qk[j] : 0.f;
     }
-    wave_lds_sync();
+    const DiagBlock dia = publish_system(a_col, m_col, a_off, m_low, a_dia, n, g);
 
     // Right-hand sides and the state's share of the read-out.
     f32x4 rhs[2], o[2];
@@ -384,18 +452,31 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
       o[1][j] = g_start[j] * w[1][j];
     }
 
+    if (more) fetch_lane(cur, at, offs, lim_next, g, n);
+
     // Forward substitution by 4-row groups (rhs turns into delta in place), then the read-out.
-    solve_rows(rhs, a_off, a_dia, n, g);
+    solve_rows(rhs, a_off, dia, n, g);
     readout_rows(o, rhs, m_low, n, g);
 
+    // Token 4g+j's output row is a scalar base of its own, the lane offset the same for all four.
+    if (whole) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int t = t0 + 4 * g + j;
-      if (t < p.T) {
+      for (int j = 0; j < 4; ++j) {
         const f32x2 y = {p.scale * o[0][j], p.scale * o[1][j]};
-        *reinterpret_cast<f32x2*>(p.out + ((row0 + t) * p.H + h) * kD + col) = y;
+        asm volatile("" : "+v"(out_off));
+        *reinterpret_cast<f32x2*>(reinterpret_cast<unsigned char*>(out_at + j * p.H * kD) + out_off) = y;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (4 * g + j <= lim) {
+          const f32x2 y = {p.scale * o[0][j], p.scale * o[1][j]};
+          asm volatile("" : "+v"(out_off));
+          *reinterpret_cast<f32x2*>(reinterpret_cast<unsigned char*>(out_at + j * p.H * kD) + out_off) = y;
+        }
       }
     }
+    out_at += kC * p.H * kD;
 
     // The stored state ends inside this chunk (a verify pass whose later tokens may be rejected): the same
     // update with the decay taken up to token n_keep-1 and the later tokens left out, written straight to memory.
@@ -417,7 +498,7 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
       }
 #pragma unroll
       for (int rt = 0; rt < 8; ++rt) {
-        const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + chn_row(16 * rt + n) + 8 * g);
+        const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + chn_row(n) + 8 * g + rt * kChRowTile);
         f32x4 acc[2];
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
@@ -455,15 +536,15 @@ __global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams
       for (int j = 0; j < 4; ++j) x[j] = g_end[j] * rhs[c][j];
       ds[c] = split2(x);
     }
+    const unsigned char* const k_lane = k_chn + chn_row(n) + 8 * g;
 #pragma unroll
     for (int rt = 0; rt < 8; ++rt) {
-      const u32x2 kt = *reinterpret_cast<const u32x2*>(k_chn + chn_row(16 * rt + n) + 8 * g);
+      const u32x2 kt = *reinterpret_cast<const u32x2*>(k_lane + rt * kChRowTile);
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         S[rt][c] = mfma_two_terms(kt, ds[c], S[rt][c]);
       }
     }
-    if (!ONE) cur = nxt;
     // The per-wavefront matrices are rewritten in the next chunk only after this chunk's reads (program order).
   }
 
@@ -506,47 +587,56 @@ struct KdaLane {
   float beta;      // of token lane%16
 };
 
-// All fetches address a uniform per-chunk base with a 32-bit lane offset (a chunk spans < 4 GiB).  Tokens
-// past the end of the call are read from the last valid token, which keeps every address in bounds; no
-// pass ever covers them, so what they hold does not matter.
-__device__ __forceinline__ void kda_fetch_raw(KdaRaw& f, const ChunkParams& p, size_t row0, int t0, int hk) {
-  const int tid = threadIdx.x;
-  const int tok = tid >> 4, c8 = (tid & 15) * 8;
+// All fetches address a uniform per-chunk base with a 32-bit lane offset (a chunk spans < 4 GiB), the offsets handled
+// as in fetch_chunk.  In the call's last, ragged chunk tokens past the end are read from the last valid token, which
+// keeps every address in bounds; no pass ever covers them, so what they hold does not matter.
+__device__ __forceinline__ void kda_fetch(KdaRaw& raw, KdaLane& f, const ChunkParams& p, ChunkOffsets& offs, size_t row0, int t0, int h,
+                                          int hk, int col, int g, int n) {
   const int lim = p.T - 1 - t0;  // last valid token of the chunk
-  const size_t base = ((row0 + t0) * p.Hk + hk) * kD;
-  const uint32_t off = (static_cast<uint32_t>(min(tok, lim)) * static_cast<uint32_t>(p.Hk * kD) + c8) * 2u;
-  f.kst = load_at<u32x4>(p.k + base, off);
-  f.qst = load_at<u32x4>(p.q + base, off);
-}
-
-__device__ __forceinline__ void kda_fetch_lane(KdaLane& f, const ChunkParams& p, size_t row0, int t0, int h, int col, int g, int n) {
-  const int lim = p.T - 1 - t0;
+  const size_t kq_base = ((row0 + t0) * p.Hk + hk) * kD;
   const size_t base = ((row0 + t0) * p.H + h);
-  const uint32_t stride = static_cast<uint32_t>(p.H * kD);
+  if (lim < kC - 1) {
+    int lim_here = lim;
+    asm volatile("" : "+s"(lim_here));  // what follows depends on this, which keeps it a branch (see fetch_staging)
+    offs = chunk_offsets(p, lim_here, col, g, n);
+  }
+  opaque(offs);
+  raw.kst = load_at<u32x4>(p.k + kq_base, offs.kq);
+  raw.qst = load_at<u32x4>(p.q + kq_base, offs.kq);
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    f.v[j] = load_at<uint32_t>(p.v + base * kD, (static_cast<uint32_t>(min(4 * g + j, lim)) * stride + col) * 2u);
-  f.beta = load_at<float>(p.beta + base, static_cast<uint32_t>(min(n, lim)) * static_cast<uint32_t>(p.H) * 4u);
+  for (int j = 0; j < 4; ++j) f.v[j] = load_at<uint32_t>(p.v + base * kD, offs.v[j]);
+  f.beta = load_at<float>(p.beta + base, offs.gate);
 }
 
-// The 16 gates of one key channel (thread tid < 128 owns channel tid).
+// The 16 gates of one key channel (thread tid < 128 owns channel tid): one scalar base for the chunk, a lane offset
+// that advances by one token row per load (and stops advancing at the call's last token).  Gates are positive, so their
+// order as floats is their order as unsigned integers; that maximum is one instruction where fmaxf is two (it first
+// quiets a signalling NaN).
 __device__ __forceinline__ void kda_fetch_gates(float (&al)[kC], const ChunkParams& p, size_t row0, int t0, int h, int chn) {
   const int lim = p.T - 1 - t0;
   const float* const base = p.alpha + ((row0 + t0) * p.H + h) * kD;
-  const uint32_t stride = static_cast<uint32_t>(p.H * kD);
+  const uint32_t stride = static_cast<uint32_t>(p.H * kD) * 4u;
+  uint32_t off = static_cast<uint32_t>(chn) * 4u;
 #pragma unroll
-  for (int t = 0; t < kC; ++t) al[t] = fmaxf(load_at<float>(base, (static_cast<uint32_t>(min(t, lim)) * stride + chn) * 4u), kMinGate);
+  for (int t = 0; t < kC; ++t) {
+    asm volatile("" : "+v"(off));
+    const uint32_t x = load_at<uint32_t>(base, off);
+    al[t] = __builtin_bit_cast(float, max(x, __builtin_bit_cast(uint32_t, kMinGate)));
+    off += t < lim ? stride : 0u;
+  }
 }
 
 __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int r = blockIdx.x / p.H;
+  // Every index here is the same for the whole workgroup; saying so keeps every base address in scalar registers
+  // (the divisions run on the vector unit and their results stay in vector registers, and everything computed
+  // from them with them, unless they are moved across by hand).
+  const int r = to_scalar(blockIdx.x / p.H);
   const int h = blockIdx.x - r * p.H;
-  // Both indices are the same for the whole workgroup; saying so keeps every base address in scalar registers.
   const int b = __builtin_amdgcn_readfirstlane(p.req_idx ? p.req_idx[r] : r);
   const int slot = __builtin_amdgcn_readfirstlane(p.slot_idx ? p.slot_idx[b] : b);
   const int n_commit = __builtin_amdgcn_readfirstlane(p.n_commit_rows ? min(max(p.n_commit_rows[b], 0), p.T) : p.n_commit);
-  const int hk = h / (p.H / p.Hk);
+  const int hk = to_scalar(h / (p.H / p.Hk));
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int n = lane & 15, g = lane >> 4;
@@ -576,8 +666,10 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
   KdaRaw raw;
   KdaLane cur, nxt;
   float gates[kC];
-  kda_fetch_raw(raw, p, row0, 0, hk);
-  kda_fetch_lane(cur, p, row0, 0, h, col, g, n);
+  // Kept in registers for the whole call (the empty asm stops the compiler from recomputing them per chunk).
+  ChunkOffsets offs = chunk_offsets(p, kC - 1, col, g, n);
+  opaque(offs);
+  kda_fetch(raw, cur, p, offs, row0, 0, h, hk, col, g, n);
   if (tid < kD) kda_fetch_gates(gates, p, row0, 0, h, chn);
   f32x4 S[8][2];
 #pragma unroll
@@ -696,18 +788,16 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
       }
 
       float beta_t[4];
-      const bool own_group = (n >> 2) == g;
+      f32x4 a_col, m_col;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int t = 4 * g + j;
         const float bt = __shfl(cur.beta, t);
         beta_t[j] = (t >= first && t < stop) ? bt : 0.f;
-        const float a = n < t ? beta_t[j] * kk[j] : 0.f;
-        a_off[t * kMatRow + n] = (n >> 2) < g ? a : 0.f;
-        a_dia[own_group ? t * 4 + (n & 3) : kC * 4 + lane] = a;
-        m_low[t * kMatRow + n] = n <= t ? qk[j] : 0.f;
+        a_col[j] = n < t ? beta_t[j] * kk[j] : 0.f;
+        m_col[j] = n <= t ? qk[j] : 0.f;
       }
-      wave_lds_sync();
+      const DiagBlock dia = publish_system(a_col, m_col, a_off, m_low, a_dia, n, g);
 
       // The next chunk's inputs are requested here, after the register-hungry products above.
       __builtin_amdgcn_sched_barrier(0);
@@ -716,8 +806,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
         // of the chunk as 64-bit vector pointers, one per load, and live (or spill) through all of it.
         int t_next = t0 + kC;
         asm volatile("" : "+s"(t_next));
-        kda_fetch_raw(raw, p, row0, t_next, hk);
-        kda_fetch_lane(nxt, p, row0, t_next, h, col, g, n);
+        kda_fetch(raw, nxt, p, offs, row0, t_next, h, hk, col, g, n);
         if (tid < kD) kda_fetch_gates(gates, p, row0, t_next, h, chn);
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -730,7 +819,7 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
       }
       o[0] = w[0];
       o[1] = w[1];
-      solve_rows(rhs, a_off, a_dia, n, g);
+      solve_rows(rhs, a_off, dia, n, g);
       readout_rows(o, rhs, m_low, n, g);
 
 #pragma unroll
@@ -744,9 +833,10 @@ __global__ __launch_bounds__(256, 2) void kda_chunk_kernel(ChunkParams p) {
 
       // S <- diag(P_end) S + Kend^T Delta.
       Split4x2 ds[2] = {split2(rhs[0]), split2(rhs[1])};
+      const int k_lane = chn_row(n) + 8 * g;
 #pragma unroll
       for (int rt = 0; rt < 8; ++rt) {
-        const int at = chn_row(16 * rt + n) + 8 * g;
+        const int at = k_lane + rt * kChRowTile;
         const u32x2 e_hi = *reinterpret_cast<const u32x2*>(kend_hi + at);
         const s16x4 e_lo = __builtin_bit_cast(s16x4, *reinterpret_cast<const u32x2*>(kend_lo + at));
         const f32x4 row_scale = *reinterpret_cast<const f32x4*>(p_end + 16 * rt + 4 * g);
