@@ -20,20 +20,20 @@
 
 namespace {
 
-// STEPS: 0 = the one-token body, else the tokens per call the multi-token body has room for.  The body for up to
-// kFewRegisterSteps tokens at 128x128 is asked to fit four wavefronts per SIMD (it does, without spilling).
+// STEPS: 0 = the one-token body, else the tokens per call the multi-token body has room for.  The multi-token body at
+// 128x128 is asked to fit four wavefronts per SIMD (it does, without spilling: 110-112 registers).
 template <int DK, int DV, bool KDA, int STEPS>
-__global__ __launch_bounds__(DV * 2, (DK == 128 && STEPS == kFewRegisterSteps) ? 4 : 1) void delta_step_kernel(DeltaParams p) {
+__global__ __launch_bounds__(DV * 2, (DK == 128 && STEPS > 0) ? 4 : 1) void delta_step_kernel(DeltaParams p) {
   __shared__ __attribute__((aligned(16))) float park[delta_park_floats<DK, DV, KDA, STEPS>()];
   delta_step_body<DK, DV, KDA, STEPS>(p, interleaved_tile(blockIdx.x, gridDim.x), blockIdx.x, park);
 }
 
 // Tokens per call from which the decode steps run on the chunk-parallel kernels, whose time hardly depends on the
-// token count up to 16 (measured at batch 64, register-resident against chunked: GDN 5 tokens 48.4 against 53 us, 6 tokens
-// 50.5 against 51.5, 7 tokens 51.5 against 51.2, 8 tokens 54 against 51.3; KDA 5 tokens 52.5 against 66 us, 6 tokens 55.8
-// against 66, 7 tokens 60 (extrapolated: its LDS room ends at 6) against 60-63, 8 tokens 62 against 61-63).  The
-// register-resident kernel holds room for 6 steps; room for 8 costs KDA a workgroup per CU (61 KiB of LDS) and 7-14 us.
-constexpr int kChunkedFromGdn = 7, kChunkedFromKda = 7;
+// token count up to 16, while the register-resident body, past the 5 or 6 tokens whose arithmetic hides behind the
+// tile's memory traffic, adds 3 (GDN) to 5 us (KDA) per token (measured at batch 64, register-resident against chunked,
+// us: GDN 6 tokens 51 against 51.5, 7 tokens 52 against 51, 8 tokens 54.4 against 51.2, 10 tokens 59.6 against 53;
+// KDA 6 tokens 51.7 against 66, 7 tokens 54.4 against 62, 8 tokens 61.1 against 61.7, 10 tokens 71 against 63.6).
+constexpr int kChunkedFromGdn = 7, kChunkedFromKda = 8;
 static_assert(kChunkedFromGdn - 1 <= kMaxRegisterSteps128 && kChunkedFromKda - 1 <= kMaxRegisterSteps128,
               "the register-resident kernel must have room for every call that is not chunked");
 
@@ -100,8 +100,6 @@ sa_status step_launch(bool dry_run, const void* q, const void* k, const void* v,
   const bool single = T == 1 && n_commit == 1 && !n_commit_rows;
   if (dk == 128 && single)
     sa::launch(kid, delta_step_kernel<128, 128, KDA, 0>, grid, dim3(256), 0, s, p);
-  else if (dk == 128 && T <= kFewRegisterSteps)
-    sa::launch(kid, delta_step_kernel<128, 128, KDA, kFewRegisterSteps>, grid, dim3(256), 0, s, p);
   else if (dk == 128)
     sa::launch(kid, delta_step_kernel<128, 128, KDA, kMaxRegisterSteps128>, grid, dim3(256), 0, s, p);
   else if (single)

@@ -47,7 +47,7 @@ using sa::DeltaParams;
 
 // Steps per call for which the multi-token tile body has LDS room at 128x128 (longer calls run on the chunk-parallel
 // kernels) and at 64x64 (the entry points' limit).
-constexpr int kMaxRegisterSteps128 = 6, kMaxRegisterSteps64 = 16, kFewRegisterSteps = 4;
+constexpr int kMaxRegisterSteps128 = 8, kMaxRegisterSteps64 = 16;
 
 // The per-step scalars and value columns of a lane as they arrive from memory (bf16 still packed).
 struct StepOperands {
@@ -78,18 +78,19 @@ struct KeyVecLds {
   }
 };
 
-// Floats of LDS one workgroup of delta_step_body needs: per wavefront and step, the parked k, q (and gate) vectors.
-// STEPS = 0: the one-token body; otherwise the multi-token body with room for STEPS tokens per call.
+// Floats of LDS one workgroup of delta_step_body needs for the parked k, q (and gate) vectors.
+// STEPS = 0: the one-token body, a copy per wavefront (so that no barrier is needed); otherwise the multi-token body
+// with room for STEPS tokens per call, one copy for the workgroup.
 template <int DK, int DV, bool KDA, int STEPS>
 constexpr int delta_park_floats() {
-  return (DV / 32) * (STEPS ? STEPS : 1) * (KDA ? 3 : 2) * KeyVecLds<DK>::kFloats;
+  return (STEPS ? STEPS : DV / 32) * (KDA ? 3 : 2) * KeyVecLds<DK>::kFloats;
 }
 
 // STEPS = 0: exactly one committed step (T == 1, n_commit == 1), the decode hot path, with an
 // unconditional store.  STEPS > 0: any T <= STEPS and any n_commit with the tile held in registers; the
-// operands of step t+1 are requested before step t is computed.  A body built for fewer steps needs fewer
-// registers and less LDS: the one for up to kFewRegisterSteps tokens (the 4-token verify pass) runs four
-// wavefronts per SIMD like the one-token body, the one for up to kMaxRegisterSteps128 three.
+// operands of step t+1 are requested before step t is computed.  Its registers do not depend on STEPS (the loop over
+// the steps is not unrolled; k, q and the gates wait in LDS), and at 128x128 it runs four wavefronts per SIMD like the
+// one-token body.
 // The work of one workgroup (2*DV threads): tile `block` = (row of the request list) * H + head.  park_lds: 16-byte
 // aligned LDS of delta_park_floats<DK, DV, KDA, STEPS>() floats.
 // EITHER (with KDA): one body for both mixers, for kernels whose workgroups run tiles of either kind: a tile with
@@ -157,28 +158,33 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   // would put a full memory latency on the critical path of every tile.
   StepOperands cur, nxt;
   load_operands<DV, KDA>(cur, p, static_cast<size_t>(b) * T, h, col0);
-  // Every wavefront fetches k and q (and KDA's gate vectors) of all its steps once, coalesced (DK values each per
-  // step), and parks them as fp32 in a region of LDS of its own; a step then reads its lane's rows from there.
-  // Per-lane global loads would fetch each value 32 times over (8 lanes and 4 wavefronts share a row): as many
-  // load instructions per 4 steps as the state tile itself takes.  No other wavefront reads the region: no barrier.
-  constexpr int kSteps = MULTI ? STEPS : 1;
+  // k and q (and KDA's gate vectors) are fetched coalesced (DK values each per step) and parked as fp32 in LDS; a step
+  // then reads its lane's rows from there.  Per-lane global loads would fetch each value 32 times over (8 lanes and 4
+  // wavefronts share a row): as many load instructions per 4 steps as the state tile itself takes.
+  // One-token body: every wavefront fetches and parks its own copy, which no other wavefront reads: no barrier.
+  // Multi-token body: one copy for the workgroup, wavefront w fetching steps w, w + (number of wavefronts), ..., and one
+  // barrier per call; a copy per wavefront of 8 steps' vectors would leave LDS for two workgroups per CU only.
+  constexpr int kWaves = DV / 32;
   constexpr int kVecs = KDA ? 3 : 2;  // k, q, gates
-  static_assert(delta_park_floats<DK, DV, KDA, STEPS>() == (DV / 32) * kSteps * kVecs * Park::kFloats);
-  float* const my_park = park_lds + wave * (kSteps * kVecs * Park::kFloats);
-  float2 gate_fetch[KDA ? kSteps : 1];
-  uint32_t k_fetch[kSteps], q_fetch[kSteps];
+  constexpr int kMine = MULTI ? (STEPS + kWaves - 1) / kWaves : 1;  // steps this wavefront fetches
+  static_assert(delta_park_floats<DK, DV, KDA, STEPS>() == (MULTI ? STEPS : kWaves) * kVecs * Park::kFloats);
+  float* const my_park = MULTI ? park_lds : park_lds + wave * (kVecs * Park::kFloats);
+  const auto fetched_step = [wave](int i) { return MULTI ? wave + i * kWaves : 0; };
+  float2 gate_fetch[KDA ? kMine : 1];
+  uint32_t k_fetch[kMine], q_fetch[kMine];
   {
     const uint32_t* const ksrc = reinterpret_cast<const uint32_t*>(p.k + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
     const uint32_t* const qsrc = reinterpret_cast<const uint32_t*>(p.q + (static_cast<size_t>(b) * T * p.Hk + hk) * DK);
     const size_t step_words = static_cast<size_t>(p.Hk) * DK / 2;
 #pragma unroll
-    for (int t = 0; t < kSteps; ++t) {
+    for (int i = 0; i < kMine; ++i) {
+      const int t = fetched_step(i);
       if (t < T) {
         if constexpr (DK == 128) {
-          k_fetch[t] = ksrc[t * step_words + lane];
-          q_fetch[t] = qsrc[t * step_words + lane];
+          k_fetch[i] = ksrc[t * step_words + lane];
+          q_fetch[i] = qsrc[t * step_words + lane];
         } else {  // 32 words each: the lower half of the wavefront fetches k, the upper half q
-          k_fetch[t] = (lane < 32 ? ksrc : qsrc)[t * step_words + (lane & 31)];
+          k_fetch[i] = (lane < 32 ? ksrc : qsrc)[t * step_words + (lane & 31)];
         }
       }
     }
@@ -186,15 +192,16 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
   if constexpr (KDA) {
     const float* const src = p.alpha + (static_cast<size_t>(b) * T * p.H + h) * DK;
 #pragma unroll
-    for (int t = 0; t < kSteps; ++t) {
+    for (int i = 0; i < kMine; ++i) {
+      const int t = fetched_step(i);
       if (t < T) {
         if (EITHER && scalar_gate) {
           const float a = load_uniform(p.alpha, (static_cast<size_t>(b) * T + t) * p.H + h);
-          gate_fetch[t] = float2{a, a};
+          gate_fetch[i] = float2{a, a};
         } else if constexpr (DK == 128) {
-          gate_fetch[t] = *reinterpret_cast<const float2*>(src + static_cast<size_t>(t) * p.H * DK + 2 * lane);
+          gate_fetch[i] = *reinterpret_cast<const float2*>(src + static_cast<size_t>(t) * p.H * DK + 2 * lane);
         } else {
-          gate_fetch[t].x = src[static_cast<size_t>(t) * p.H * DK + lane];
+          gate_fetch[i].x = src[static_cast<size_t>(t) * p.H * DK + lane];
         }
       }
     }
@@ -210,26 +217,30 @@ __device__ __forceinline__ void delta_step_body(const DeltaParams& p, const int 
     const int at0 = Park::slot(pair_row, rot), at1 = Park::slot(pair_row + 1, rot);
     const int vec = DK == 128 ? 0 : (lane >> 5) * Park::kFloats;  // DK = 64: the upper half writes into q's vector
 #pragma unroll
-    for (int t = 0; t < kSteps; ++t) {
+    for (int i = 0; i < kMine; ++i) {
+      const int t = fetched_step(i);
       if (t < T) {
         float* const base = my_park + t * (kVecs * Park::kFloats);
-        base[vec + at0] = bf16_lo(k_fetch[t]);
-        base[vec + at1] = bf16_hi(k_fetch[t]);
+        base[vec + at0] = bf16_lo(k_fetch[i]);
+        base[vec + at1] = bf16_hi(k_fetch[i]);
         if constexpr (DK == 128) {
-          base[Park::kFloats + at0] = bf16_lo(q_fetch[t]);
-          base[Park::kFloats + at1] = bf16_hi(q_fetch[t]);
+          base[Park::kFloats + at0] = bf16_lo(q_fetch[i]);
+          base[Park::kFloats + at1] = bf16_hi(q_fetch[i]);
         }
         if constexpr (KDA) {
           if constexpr (DK == 128) {
-            base[2 * Park::kFloats + at0] = gate_fetch[t].x;
-            base[2 * Park::kFloats + at1] = gate_fetch[t].y;
+            base[2 * Park::kFloats + at0] = gate_fetch[i].x;
+            base[2 * Park::kFloats + at1] = gate_fetch[i].y;
           } else {
-            base[2 * Park::kFloats + Park::slot(lane, rot)] = gate_fetch[t].x;
+            base[2 * Park::kFloats + Park::slot(lane, rot)] = gate_fetch[i].x;
           }
         }
       }
     }
-    wave_lds_sync();
+    if constexpr (MULTI)
+      __syncthreads();  // every wavefront of the workgroup reaches this: the body has no early exit
+    else
+      wave_lds_sync();
   }
 
   if (MULTI && n_commit == 0 && p.state_out != p.state_in) {

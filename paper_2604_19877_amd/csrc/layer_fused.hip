@@ -59,9 +59,9 @@ __device__ __forceinline__ void run_tile(const sa::DeltaParams& kda, const sa::D
     delta_step_body<128, 128, true, 0, true>(is_gdn ? gdn : kda, is_gdn ? tile - n_kda : tile, blockIdx.x, park, is_gdn);
   } else {
     if (tile >= n_kda)
-      delta_step_body<128, 128, false, kFewRegisterSteps>(gdn, tile - n_kda, blockIdx.x, park);
+      delta_step_body<128, 128, false, kMaxRegisterSteps128>(gdn, tile - n_kda, blockIdx.x, park);
     else
-      delta_step_body<128, 128, true, kFewRegisterSteps>(kda, tile, blockIdx.x, park);
+      delta_step_body<128, 128, true, kMaxRegisterSteps128>(kda, tile, blockIdx.x, park);
   }
 }
 
@@ -82,7 +82,7 @@ template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_decode_kernel(LayerParams p) {
   __shared__ AttnShared sm;
   // one region for whichever tile body this workgroup runs (the KDA body needs the larger one)
-  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI ? kFewRegisterSteps : 0>()];
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI ? kMaxRegisterSteps128 : 0>()];
   const int id = blockIdx.x;
   if (id < p.end_prev) {
     merge_items(p.prev, 2 * id);
@@ -113,7 +113,7 @@ struct RecurrentLayerParams {
 
 template <bool MULTI>
 __global__ __launch_bounds__(256) void layer_recurrent_kernel(RecurrentLayerParams p) {
-  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI ? kFewRegisterSteps : 0>()];
+  __shared__ __attribute__((aligned(16))) float park[delta_park_floats<128, 128, true, MULTI ? kMaxRegisterSteps128 : 0>()];
   if (static_cast<int>(blockIdx.x) < p.end_prev) {
     merge_items(p.prev, 2 * blockIdx.x);
     return;
