@@ -105,8 +105,8 @@ sa_status sa_state_unpack(const float* tiles, float* rowmajor, int n_tiles, int 
  * chained single steps up to rounding: every fp32 operand of a product enters as two bf16 terms (relative
  * error 2^-18), which leaves outputs and states about 1e-5 from the fp64 recurrence.  Arguments as for the
  * decode steps (n_commit included: all T outputs are produced, the state written is the one after n_commit
- * tokens); any T >= 1.  The decode steps themselves run on these kernels from 7 tokens per call at
- * (dk,dv) = (128,128), where they are as fast or faster (8 tokens: 51 / 62 us against 54 / 62 us at batch 64).  Gates below 2^-100 act as 2^-100 in kda_chunk_steps and below the smallest
+ * tokens); any T >= 1.  The decode steps themselves run on these kernels from 7 (GDN) or 8 (KDA) tokens per call at
+ * (dk,dv) = (128,128), where they are as fast or faster (8 tokens: 51 / 61 us against 54 / 61 us at batch 64).  Gates below 2^-100 act as 2^-100 in kda_chunk_steps and below the smallest
  * normal fp32 number as that number in gdn_chunk_steps.  Supported: (dk,dv) = (128,128).
  */
 sa_status gdn_chunk_steps(const void* q, const void* k, const void* v, const float* alpha, const float* beta,
