@@ -299,10 +299,11 @@ __device__ __forceinline__ void fetch_lane(ChunkFetch& f, const ChunkBases& at, 
 }
 
 // ONE: the call is a single chunk (T <= 16, a verify pass): nothing is prefetched for a next chunk and one staging
-// buffer is enough, which leaves registers and LDS for a third wavefront per SIMD (8 tokens at batch 64: 51 us
-// against 54 us; a kernel of many chunks forced to the same register budget spills and runs 60 % slower).
+// buffer is enough (144 registers, 26 KiB of LDS).  Both forms are held to three wavefronts per SIMD (168 registers),
+// which the kernel of many chunks just fits without spilling (41 KiB of LDS; 8 tokens at batch 64: 51 us against 54 us
+// with two wavefronts, 512 tokens 10 % faster).
 template <bool ONE>
-__global__ __launch_bounds__(256, ONE ? 3 : 2) void gdn_chunk_kernel(ChunkParams p) {
+__global__ __launch_bounds__(256, 3) void gdn_chunk_kernel(ChunkParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   // Every index here is the same for the whole workgroup; saying so keeps every base address in scalar registers
   // (the divisions run on the vector unit and their results stay in vector registers, and everything computed
