@@ -89,7 +89,7 @@ sa_status kda_decode_step_var(const void* q, const void* k, const void* v, const
                               const int32_t* n_commit_rows, void* stream);
 
 /* State tiles.  A recurrent state is dk*dv fp32 values per (slot, head); callers that do not want to depend on the
- * order inside a tile convert with these (Appendix B: "a state matrix S in R^{dk x dv}" per head).  In this library a
+ * order inside a tile convert with these (Appendix B: one dk x dv state matrix per head).  In this library a
  * tile is plain row-major [dk][dv] (key channel major), so both conversions are copies; they exist so that the order
  * can change without breaking callers.  rowmajor and tiles: device pointers, n_tiles * dk * dv floats each, 16-byte
  * aligned, not overlapping.  (dk,dv) as for the decode steps. */
@@ -99,8 +99,8 @@ sa_status sa_state_unpack(const float* tiles, float* rowmajor, int n_tiles, int 
 
 /* ---------------------------------------------------------------------------------------------
  * Many tokens per state pass: the same recurrences and read-out as gdn_decode_step / kda_decode_step,
- * evaluated in their chunk-parallel form (Appendix B: GDN runs "chunkwise" on a WY representation, KDA on
- * DPLR transitions; Section 6: chunkwise kernels serve prefill).  Tokens are processed 16 at a time as matrix
+ * evaluated in their chunk-parallel form (Appendix B: GDN is evaluated chunk by chunk on a WY representation, KDA on
+ * DPLR transitions; Section 6: such kernels serve prefill).  Tokens are processed 16 at a time as matrix
  * products on the matrix cores with the state held in registers across the whole call.  Results equal T
  * chained single steps up to rounding: every fp32 operand of a product enters as two bf16 terms (relative
  * error 2^-18), which leaves outputs and states about 1e-5 from the fp64 recurrence.  Arguments as for the

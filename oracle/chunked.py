@@ -1,7 +1,7 @@
 """Chunk-parallel form of the GDN / KDA recurrences in fp64 (test infrastructure only).
 
-Appendix B of the paper says GDN trains "with a chunkwise parallel algorithm based on the WY
-representation" and KDA with "DPLR transition matrices"; Section 6 uses such chunkwise kernels for
+Appendix B of the paper names the parallel forms the mixers train with (GDN: chunk by chunk on a WY
+representation; KDA: diagonal-plus-low-rank transition matrices) and Section 6 uses such kernels for
 prefill.  The paper prints neither, so this is a derivation from the printed recurrences:
 
 with Gamma_t = prod_{i<=t} alpha_i inside the chunk (a scalar for GDN, a vector over key channels for

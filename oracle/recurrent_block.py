@@ -5,7 +5,7 @@ Appendix B of the paper lists, for GDN: a short causal 1-D convolution with SiLU
 the recurrence, L2-normalised queries and keys, beta = sigmoid(beta_raw),
 g = -exp(A_log) * softplus(alpha_raw + dt_bias) as the log-decay (alpha = exp(g)), and a gated RMS
 normalisation of the read-out with z as the gate; for KDA: the same with one convolution per stream,
-a per-key-channel gate from "the fused gate computation" and a separate output gate.  The paper gives
+a per-key-channel gate that comes out of one fused gate computation, and a separate output gate.  The paper gives
 no formula for the normalisation or for KDA's gate; the readings taken are
   * L2 norm:   x / sqrt(sum(x^2) + 1e-6) per head,
   * KDA gate:  the GDN formula per channel, A_log per head and dt_bias per (head, channel),

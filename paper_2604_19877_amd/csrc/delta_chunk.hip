@@ -1,6 +1,6 @@
 // Chunk-parallel form of the GDN recurrence on the matrix cores, gfx950: many tokens per state pass.
 //
-// Appendix B of the paper says GDN runs "chunkwise" on a WY representation for long inputs and
+// Appendix B of the paper has GDN evaluated chunk by chunk on a WY representation for long inputs and
 // Section 6 uses such kernels for prefill; the paper prints only the token-by-token recurrence
 //     S_t = alpha_t (I - beta_t k_t k_t^T) S_{t-1} + beta_t k_t v_t^T,      o_t = scale S_t^T q_t.
 // Unrolled over a chunk of C = 16 tokens with g(t,i) = prod_{i<m<=t} alpha_m  (g(t,t) = 1,
