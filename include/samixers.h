@@ -62,7 +62,7 @@ int sa_version(void);
  *   req_idx   int32 [n_req] or NULL: the batch rows to process (NULL = rows 0..B-1, n_req ignored);
  *             rows not listed are not touched.  A row must not be listed twice.
  * Supported: (dk,dv) in {(64,64),(128,128)}, 1 <= T <= 16.  B = 0 or n_req = 0 is a no-op.
- * At (128,128) calls of 7 and more tokens are evaluated in the chunk-parallel form (see
+ * At (128,128) calls of 7 (gdn) / 8 (kda) and more tokens are evaluated in the chunk-parallel form (see
  * gdn_chunk_steps): same arguments and results, outputs and states about 1e-5 instead of 1e-6 from the fp64 recurrence.
  */
 sa_status gdn_decode_step(const void* q, const void* k, const void* v, const float* alpha, const float* beta,

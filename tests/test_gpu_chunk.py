@@ -248,7 +248,7 @@ def test_committed_prefix_of_a_chunked_call(kda, n_commit, in_place):
 
 @pytest.mark.parametrize("kda", KINDS)
 def test_decode_step_with_eight_tokens_runs_on_the_chunk_kernels_and_keeps_its_contract(kda):
-    """gdn_decode_step / kda_decode_step hand longer calls (from 6 / 7 tokens) to the chunk-parallel kernels: an 8-token
+    """gdn_decode_step / kda_decode_step hand longer calls (from 7 / 8 tokens) to the chunk-parallel kernels: an 8-token
     verify with 3 accepted tokens, out of place."""
     B, H, T, n_commit = 3, 4, 8, 3
     p = gen.recurrent_inputs(4950 + kda, B, T, H, H, 128, 128, kda)
