@@ -219,7 +219,7 @@ def test_stream_tiles_calibration_kernel_touches_exactly_its_tiles():
 @pytest.mark.parametrize("T,dk", [(4, 128), (5, 128), (6, 128), (7, 128), (8, 128), (13, 128), (3, 64), (16, 64), (1, 128)])
 def test_per_request_commit_counts(kda, T, dk):
     """Every request commits its own number of drafted tokens in one call (short calls on the register-resident kernel,
-    longer ones, from 6 tokens for GDN and 7 for KDA at 128x128, on the chunk-parallel one); counts outside [0, T] are
+    longer ones, from 7 tokens for GDN and 8 for KDA at 128x128, on the chunk-parallel one); counts outside [0, T] are
     clamped; unlisted rows stay untouched."""
     B, H, Hk, dv = 7, 4, 2, dk
     p = gen.recurrent_inputs(1600 + T + kda, B, T, H, Hk, dk, dv, kda)
